@@ -1,0 +1,124 @@
+"""numpy front end of the CPU oracle (oracle/kvq_oracle.c).
+
+TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only tests/, __graft_entry__.smoke() and
+bench.py's cpu_baseline leg may import this package.  It holds no code of the
+HIP library and the HIP library holds none of it.
+
+All arrays are C-contiguous numpy arrays; a matrix is [N, D] (tokens x
+channels) or [batch, N, D]; scales are [D] or [batch, D].
+"""
+import ctypes
+import threading
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+_lock = threading.Lock()
+
+_i64 = ctypes.c_int64
+_fp = ctypes.POINTER(ctypes.c_float)
+_bp = ctypes.POINTER(ctypes.c_int8)
+_dp = ctypes.POINTER(ctypes.c_double)
+
+
+def lib():
+    """Load (building first if the source is newer) the oracle shared library."""
+    global _lib
+    with _lock:
+        if _lib is None:
+            path = _build.build(force=False)
+            L = ctypes.CDLL(path)
+            L.kvq_oracle_compute_scales.argtypes = [_fp, _fp, _i64, _i64, _i64]
+            L.kvq_oracle_compute_scales.restype = None
+            L.kvq_oracle_quantize.argtypes = [_fp, _fp, _bp, _i64, _i64, _i64]
+            L.kvq_oracle_quantize.restype = None
+            L.kvq_oracle_dequantize.argtypes = [_bp, _fp, _fp, _i64, _i64, _i64]
+            L.kvq_oracle_dequantize.restype = None
+            L.kvq_oracle_roundtrip_error.argtypes = [_fp, _fp, _i64, _dp, _fp]
+            L.kvq_oracle_roundtrip_error.restype = None
+            L.kvq_oracle_attn_score_error.argtypes = [_fp, _i64, _fp, _fp, _i64, _i64, _dp]
+            L.kvq_oracle_attn_score_error.restype = None
+            _lib = L
+    return _lib
+
+
+def _shape3(a):
+    if a.ndim == 2:
+        return 1, a.shape[0], a.shape[1]
+    if a.ndim == 3:
+        return a.shape
+    raise ValueError("expected [N, D] or [batch, N, D], got shape %r" % (a.shape,))
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32:
+        raise TypeError("expected float32, got %s" % a.dtype)
+    return a
+
+
+def _ptr(a, t):
+    return a.ctypes.data_as(t)
+
+
+def compute_scales(x):
+    """scales[b, d] = max_t |x[b, t, d]| / 127 (fp32)."""
+    x = _f32(x)
+    b, n, d = _shape3(x)
+    out = np.empty((b, d), dtype=np.float32)
+    lib().kvq_oracle_compute_scales(_ptr(x, _fp), _ptr(out, _fp), b, n, d)
+    return out if x.ndim == 3 else out[0]
+
+
+def quantize(x, scales):
+    """codes = clamp(rint(x / scale), -127, 127) as int8; 0 where scale == 0."""
+    x = _f32(x)
+    scales = _f32(scales)
+    b, n, d = _shape3(x)
+    if scales.size != b * d:
+        raise ValueError("scales must hold batch*D values")
+    out = np.empty(x.shape, dtype=np.int8)
+    lib().kvq_oracle_quantize(_ptr(x, _fp), _ptr(scales, _fp), _ptr(out, _bp), b, n, d)
+    return out
+
+
+def dequantize(codes, scales):
+    """x_hat = float(code) * scale (fp32)."""
+    codes = np.ascontiguousarray(codes)
+    if codes.dtype != np.int8:
+        raise TypeError("expected int8 codes")
+    scales = _f32(scales)
+    b, n, d = _shape3(codes)
+    if scales.size != b * d:
+        raise ValueError("scales must hold batch*D values")
+    out = np.empty(codes.shape, dtype=np.float32)
+    lib().kvq_oracle_dequantize(_ptr(codes, _bp), _ptr(scales, _fp), _ptr(out, _fp), b, n, d)
+    return out
+
+
+def roundtrip_error(x, x_hat):
+    """Returns (sumsq: float64, maxabs: float32) of x - x_hat over all elements."""
+    x = _f32(x)
+    x_hat = _f32(x_hat)
+    if x.shape != x_hat.shape:
+        raise ValueError("shape mismatch")
+    s = ctypes.c_double(0.0)
+    m = ctypes.c_float(0.0)
+    lib().kvq_oracle_roundtrip_error(_ptr(x, _fp), _ptr(x_hat, _fp), x.size,
+                                     ctypes.byref(s), ctypes.byref(m))
+    return float(s.value), np.float32(m.value)
+
+
+def attn_score_error(queries, k, k_hat):
+    """mean over (query j, token t) of |q_j . k_t - q_j . k_hat_t| (fp64)."""
+    queries = _f32(queries)
+    k = _f32(k)
+    k_hat = _f32(k_hat)
+    if k.ndim != 2 or k.shape != k_hat.shape or queries.ndim != 2 or queries.shape[1] != k.shape[1]:
+        raise ValueError("expected queries [Q, D], k and k_hat [N, D]")
+    r = ctypes.c_double(0.0)
+    lib().kvq_oracle_attn_score_error(_ptr(queries, _fp), queries.shape[0], _ptr(k, _fp),
+                                      _ptr(k_hat, _fp), k.shape[0], k.shape[1], ctypes.byref(r))
+    return float(r.value)

@@ -1,0 +1,349 @@
+"""Pins of the CPU oracle against things other than itself.
+
+Each test checks oracle/ against what the paper or the mathematics fixes:
+hand-worked examples, exact rational arithmetic, brute force over candidate
+scales, the error figures the paper prints (tests/golden/), closed forms,
+invariants, and special cases that reduce to numpy routines.  CPU only.
+"""
+from fractions import Fraction
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2601_04719_amd import workloads
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if line:
+                k, v = line.split("=")
+                out[k.strip()] = float(v)
+    return out
+
+
+# --------------------------------------------------------------------------
+# exact helpers (integers and Fractions only; no floating-point arithmetic)
+# --------------------------------------------------------------------------
+def round_half_even(fr: Fraction) -> int:
+    fl = fr.numerator // fr.denominator
+    rem = fr - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
+def fl32(fr: Fraction) -> Fraction:
+    """Nearest binary32 value (ties to even, gradual underflow) of an exact rational."""
+    if fr == 0:
+        return Fraction(0)
+    sign = -1 if fr < 0 else 1
+    a = abs(fr)
+    e = a.numerator.bit_length() - a.denominator.bit_length()   # 2^(e-1) < a < 2^(e+1)
+    if Fraction(2) ** e > a:
+        e -= 1
+    e = max(e, -126)                       # below 2^-126 the spacing stays 2^-149
+    ulp = Fraction(2) ** (e - 23)
+    m = round_half_even(a / ulp)
+    r = m * ulp
+    assert r < Fraction(2) ** 128, "overflow not expected in these tests"
+    return sign * r
+
+
+def exact_code(x: np.float32, s: np.float32) -> int:
+    """Eq. (quant_op) + clamp, evaluated exactly: divide, round once to fp32, round to even."""
+    if s == 0:
+        return 0
+    q32 = fl32(Fraction(float(x)) / Fraction(float(s)))
+    return max(-127, min(127, round_half_even(q32)))
+
+
+# --------------------------------------------------------------------------
+# P1  hand-worked examples
+# --------------------------------------------------------------------------
+def test_hand_worked_4x3():
+    # column 0: absmax 127 -> s = 1; quotients 127, .5, 1.5, -2.5: ties go to even (0, 2, -2)
+    # column 1: all zero   -> s = 0; codes 0; reconstruction +0
+    # column 2: absmax is the NEGATIVE entry -254 -> s = 2; quotients -1, .25, -127, 1.5 -> -1, 0, -127, 2
+    x = np.array([[127.0, 0.0, -2.0],
+                  [0.5, 0.0, 0.5],
+                  [1.5, 0.0, -254.0],
+                  [-2.5, 0.0, 3.0]], dtype=np.float32)
+    s = oracle.compute_scales(x)
+    assert s.dtype == np.float32 and s.tolist() == [1.0, 0.0, 2.0]
+    q = oracle.quantize(x, s)
+    assert q.dtype == np.int8
+    assert q.tolist() == [[127, 0, -1], [0, 0, 0], [2, 0, -127], [-2, 0, 2]]
+    xh = oracle.dequantize(q, s)
+    assert xh.tolist() == [[127.0, 0.0, -2.0], [0.0, 0.0, 0.0], [2.0, 0.0, -254.0], [-2.0, 0.0, 4.0]]
+    assert not np.signbit(xh[:, 1]).any()
+    # x - xh = [[0,0,0],[.5,0,.5],[-.5,0,0],[-.5,0,-1]] -> squares sum 4*.25 + 1 = 2; max 1
+    sumsq, maxabs = oracle.roundtrip_error(x, xh)
+    assert sumsq == 2.0 and maxabs == 1.0
+    # queries (1,0,0) and (1,1,-1): per-token score differences
+    #   q0: 0, .5, -.5, -.5 -> |.| sums to 1.5 ;  q1: 0, .5-.5=0, -.5, -.5+1=.5 -> 1.0
+    qs = np.array([[1, 0, 0], [1, 1, -1]], dtype=np.float32)
+    assert oracle.attn_score_error(qs, x, xh) == pytest.approx(2.5 / 8, abs=1e-15)
+
+
+def test_hand_worked_4x4_power_of_two_scales():
+    # scales 1/8, 4, 2^-10, 1: absmax = 127 * scale exactly, so every quotient below is exact
+    sc = [0.125, 4.0, 2.0 ** -10, 1.0]
+    quot = np.array([[127.0, -3.5, 0.5, -0.5],
+                     [2.5, 127.0, -1.5, 126.5],
+                     [-6.5, 0.49, -127.0, -127.0],
+                     [0.75, -126.5, 63.5, 4.5]])
+    x = (quot * np.array(sc)).astype(np.float32)
+    # the entry 0.49 * 4 = 1.96 is not exact in binary; its quotient is still far from a tie
+    expect = [[127, -4, 0, 0], [2, 127, -2, 126], [-6, 0, -127, -127], [1, -126, 64, 4]]
+    s = oracle.compute_scales(x)
+    assert s.tolist() == sc
+    q = oracle.quantize(x, s)
+    assert q.tolist() == expect
+    xh = oracle.dequantize(q, s)
+    assert xh.tolist() == (np.array(expect) * np.array(sc)).tolist()
+
+
+def test_batched_slabs_have_independent_scales():
+    # two [2 x 2] slabs; a transposed or shared-scale implementation fails this
+    x = np.array([[[127.0, 2.0], [1.0, -254.0]],
+                  [[12.7, 0.0], [-1270.0, 0.0]]], dtype=np.float32)
+    s = oracle.compute_scales(x)
+    assert s.shape == (2, 2)
+    assert s[0].tolist() == [1.0, 2.0]
+    assert s[1, 1] == 0.0 and s[1, 0] == np.float32(1270.0) / np.float32(127.0)
+    q = oracle.quantize(x, s)
+    assert q[0].tolist() == [[127, 1], [1, -127]]
+    assert q[1].tolist() == [[1, 0], [-127, 0]]
+
+
+def test_one_by_one_and_signed_zero():
+    x = np.array([[-3.0]], dtype=np.float32)
+    s = oracle.compute_scales(x)
+    assert s[0] == np.float32(3.0) / np.float32(127.0)
+    assert oracle.quantize(x, s).tolist() == [[-127]]
+    z = np.array([[-0.0, 0.0]], dtype=np.float32)
+    sz = oracle.compute_scales(z)
+    assert sz.tolist() == [0.0, 0.0] and not np.signbit(sz).any()
+    assert oracle.quantize(z, sz).tolist() == [[0, 0]]
+
+
+def test_structured_patterns():
+    # the degenerate patterns the paper's unit tests name: all ones, alternating signs
+    ones = np.ones((5, 7), dtype=np.float32)
+    s = oracle.compute_scales(ones)
+    assert (s == np.float32(1.0) / np.float32(127.0)).all()
+    assert (oracle.quantize(ones, s) == 127).all()
+    alt = ones.copy()
+    alt[1::2] = -1.0
+    q = oracle.quantize(alt, oracle.compute_scales(alt))
+    assert (q[0::2] == 127).all() and (q[1::2] == -127).all()
+
+
+# --------------------------------------------------------------------------
+# P4  exact rational arithmetic and brute force over scales
+# --------------------------------------------------------------------------
+def test_division_and_rounding_against_exact_rationals():
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal((48, 9)) * np.exp(rng.uniform(-3, 3, 9))).astype(np.float32)
+    # make ties and near-ties certain: column 8 is multiples of half its scale
+    x[:, 8] = (np.arange(48) - 24) * 0.5 * 0.03125
+    x[0, 8] = 127 * 0.03125
+    s = oracle.compute_scales(x)
+    q = oracle.quantize(x, s)
+    xh = oracle.dequantize(q, s)
+    for d in range(x.shape[1]):
+        absmax = max(abs(Fraction(float(v))) for v in x[:, d])
+        assert Fraction(float(s[d])) == fl32(absmax / 127)
+        for t in range(x.shape[0]):
+            assert int(q[t, d]) == exact_code(x[t, d], s[d]), (t, d)
+            assert Fraction(float(xh[t, d])) == fl32(int(q[t, d]) * Fraction(float(s[d])))
+    assert s[8] == 0.03125 and set(q[:, 8].tolist()) >= {-12, -10, 0, 2, 4, 127}
+
+
+def test_exact_rationals_with_given_scales_that_clip():
+    # scales smaller than absmax/127 (a caller may pass any scale): the clamp must engage
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((32, 4)).astype(np.float32)
+    s = np.array([0.001, 0.01, 1e-30, 3.0], dtype=np.float32)
+    q = oracle.quantize(x, s)
+    for d in range(4):
+        for t in range(32):
+            assert int(q[t, d]) == exact_code(x[t, d], s[d])
+    assert (np.abs(q[:, 2]) == 127).all() and q.min() == -127 and q.max() == 127
+
+
+def test_scale_is_the_smallest_that_needs_no_clamp_brute_force():
+    rng = np.random.default_rng(3)
+    for trial in range(20):
+        col = (rng.standard_normal(8) * 10.0 ** rng.uniform(-2, 2)).astype(np.float32)
+        x = col[:, None].copy()
+        s = float(oracle.compute_scales(x)[0])
+        absmax = float(np.abs(col).max())
+        for f in np.linspace(0.5, 2.0, 61):
+            cand = np.array([s * f], dtype=np.float32)
+            q = oracle.quantize(x, cand)
+            xh = oracle.dequantize(q, cand)
+            err = np.abs(x.astype(np.float64) - xh.astype(np.float64)).max()
+            c = float(cand[0])
+            if f >= 1.0:
+                # no element needs the clamp and the bound of Eq. (error_bound) holds
+                assert absmax / c <= 127.0 * (1 + 1e-6)
+                assert err <= c / 2 * (1 + 2.0 ** -15)
+            elif f <= 0.99:
+                # a smaller scale clips the absmax element: error absmax - 127*c > s/2 * (254 (1-f))
+                assert np.abs(q).max() == 127
+                assert err == pytest.approx(absmax - 127.0 * c, rel=1e-5)
+        # 127 quantization steps of the chosen scale reach absmax (and 126.5 do not)
+        assert 126.5 * s < absmax <= 127.0 * s * (1 + 2.0 ** -22)
+
+
+# --------------------------------------------------------------------------
+# P2, P3  invariants on realistic data
+# --------------------------------------------------------------------------
+def test_invariants_on_config1():
+    x = workloads.generate(1)[0]
+    s = oracle.compute_scales(x)
+    q = oracle.quantize(x, s)
+    xh = oracle.dequantize(q, s)
+    # every nonzero channel reaches a code of exactly +-127 at its absmax element
+    am = np.abs(x).argmax(axis=0)
+    assert (np.abs(q[am, np.arange(x.shape[1])]) == 127).all()
+    assert np.abs(q.astype(np.int32)).max() == 127
+    # Eq. (error_bound): |x - xhat| <= s/2, with the slack fp32 division needs near ties
+    err = np.abs(x.astype(np.float64) - xh.astype(np.float64))
+    assert (err <= s.astype(np.float64)[None, :] / 2 * (1 + 2.0 ** -15)).all()
+    # codes carry the sign of x (or are zero)
+    assert ((np.sign(q) == np.sign(x)) | (q == 0)).all()
+
+
+def test_subnormal_scales():
+    tiny = np.float32(2.0 ** -149)
+    x = np.zeros((3, 3), dtype=np.float32)
+    x[:, 0] = [100 * tiny, -37 * tiny, tiny]      # absmax/127 = .787 ulp -> s = 2^-149 (subnormal)
+    x[:, 1] = [50 * tiny, -50 * tiny, 3 * tiny]   # absmax/127 = .394 ulp -> s underflows to 0
+    x[:, 2] = [1.0, tiny, -tiny]                  # ordinary scale, subnormal entries -> code 0
+    s = oracle.compute_scales(x)
+    assert s[0] == tiny and s[1] == 0.0
+    q = oracle.quantize(x, s)
+    assert q[:, 0].tolist() == [100, -37, 1]
+    assert q[:, 1].tolist() == [0, 0, 0]
+    assert q[:, 2].tolist() == [127, 0, 0]
+    xh = oracle.dequantize(q, s)
+    assert xh[:, 0].tolist() == x[:, 0].tolist()
+
+
+# --------------------------------------------------------------------------
+# P5, P6  the figures the paper prints
+# --------------------------------------------------------------------------
+def test_paper_max_abs_error_for_unit_inputs():
+    g = golden("paper_error_figures.txt")
+    for (n, d) in [(2048, 128), (512, 1024)]:
+        x = workloads.uniform_matrix(n, d, seed=1)
+        s = oracle.compute_scales(x)
+        xh = oracle.dequantize(oracle.quantize(x, s), s)
+        _, maxabs = oracle.roundtrip_error(x, xh)
+        assert abs(float(maxabs) - g["max_abs_error_unit_inputs"]) < 5e-6      # printed to 3 digits
+        assert float(maxabs) < g["max_abs_error_bound"]
+        assert float(maxabs) <= 1.0 / 254.0 * (1 + 1e-4)
+
+
+def _attn_err_uniform(n, d, nq, seed):
+    k = workloads.uniform_matrix(n, d, seed=seed, stream=0)
+    qs = workloads.uniform_matrix(nq, d, seed=seed, stream=1)
+    s = oracle.compute_scales(k)
+    kh = oracle.dequantize(oracle.quantize(k, s), s)
+    return oracle.attn_score_error(qs, k, kh)
+
+
+def test_paper_attention_error_at_8192_and_sqrt_scaling():
+    g = golden("paper_error_figures.txt")
+    e8k = _attn_err_uniform(512, 8192, 16, seed=2)
+    assert abs(e8k - g["attn_score_error_D8192"]) < 0.0025          # printed as 0.095
+    assert e8k < g["attn_score_error_bound_D8192"]
+    e2k = _attn_err_uniform(2048, 2048, 16, seed=3)
+    e512 = _attn_err_uniform(4096, 512, 16, seed=4)
+    slope = math.log(e8k / e512) / math.log(8192 / 512)
+    assert abs(slope - g["attn_score_error_D_exponent"]) < 0.03
+    assert e2k == pytest.approx(math.sqrt(e8k * e512), rel=0.05)
+
+
+# --------------------------------------------------------------------------
+# P7  closed forms under uniform rounding error
+# --------------------------------------------------------------------------
+def test_l2_and_score_error_closed_forms():
+    c = workloads.CONFIGS[1]
+    x = workloads.generate(1)[0]
+    qs = workloads.queries(1)
+    s = oracle.compute_scales(x)
+    xh = oracle.dequantize(oracle.quantize(x, s), s)
+    sumsq, _ = oracle.roundtrip_error(x, xh)
+    s64 = s.astype(np.float64)
+    # rounding error uniform in [-s/2, s/2]: E[e^2] = s^2/12 per element
+    assert math.sqrt(sumsq) == pytest.approx(math.sqrt(c.N * (s64 ** 2).sum() / 12), rel=0.02)
+    # score difference = sum_d q_d e_d ~ Normal(0, sum_d q_d^2 s_d^2/12); E|.| = sqrt(2/pi) sigma
+    sig = np.sqrt(((qs.astype(np.float64) ** 2) * (s64 ** 2)[None, :] / 12).sum(axis=1))
+    assert oracle.attn_score_error(qs, x, xh) == pytest.approx(math.sqrt(2 / math.pi) * sig.mean(), rel=0.03)
+
+
+# --------------------------------------------------------------------------
+# P8  identity
+# --------------------------------------------------------------------------
+def test_identity_metrics_are_zero():
+    x = workloads.generate(1)[0]
+    assert oracle.roundtrip_error(x, x) == (0.0, 0.0)
+    assert oracle.attn_score_error(workloads.queries(1), x, x) == 0.0
+
+
+# --------------------------------------------------------------------------
+# P9  special cases that reduce to numpy routines
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,rows", [(1, (0, 1024)), (2, (0, 4096)), (4, (0, 256)), (5, (0, 256))])
+def test_against_numpy_routines(cfg, rows):
+    x = workloads.generate(cfg, rows=rows)[0]
+    s = oracle.compute_scales(x)
+    assert np.array_equal(s, np.abs(x).max(axis=0) / np.float32(127.0))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.rint(x / s[None, :])
+    ref = np.where(s[None, :] == 0, np.float32(0), np.clip(r, -127, 127)).astype(np.int8)
+    q = oracle.quantize(x, s)
+    assert np.array_equal(q, ref)
+    xh = oracle.dequantize(q, s)
+    assert np.array_equal(xh, q.astype(np.float32) * s[None, :])
+    sumsq, maxabs = oracle.roundtrip_error(x, xh)
+    e = x - xh
+    assert maxabs == np.abs(e).max()
+    assert sumsq == pytest.approx(float((e.astype(np.float64) ** 2).sum()), rel=1e-12)
+    if cfg == 5:
+        zero = workloads.special_channels(workloads.CONFIGS[5])
+        assert len(zero) == 82 and (s[zero] == 0).all() and (q[:, zero] == 0).all()
+        assert np.count_nonzero(s == 0) == 82
+
+
+def test_score_error_against_numpy_matmul():
+    x = workloads.generate(2, rows=(0, 2048))[0]
+    qs = workloads.queries(2)
+    s = oracle.compute_scales(x)
+    xh = oracle.dequantize(oracle.quantize(x, s), s)
+    a = qs.astype(np.float64) @ x.astype(np.float64).T
+    b = qs.astype(np.float64) @ xh.astype(np.float64).T
+    assert oracle.attn_score_error(qs, x, xh) == pytest.approx(np.abs(a - b).mean(), rel=1e-10)
+
+
+def test_batched_equals_per_slab():
+    x = workloads.generate(3, slabs=(30, 34), rows=(0, 512))
+    s = oracle.compute_scales(x)
+    q = oracle.quantize(x, s)
+    xh = oracle.dequantize(q, s)
+    for b in range(x.shape[0]):
+        sb = oracle.compute_scales(x[b])
+        assert np.array_equal(sb, s[b])
+        assert np.array_equal(oracle.quantize(x[b], sb), q[b])
+        assert np.array_equal(oracle.dequantize(q[b], sb), xh[b])
