@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the INT8 KV-cache quantization hot path on one MI355X.
+
+A step is one pass of the whole path over one resident batch:
+    kvq_absmax_scales -> kvq_quantize -> kvq_dequantize -> kvq_roundtrip_error (x vs x_hat)
+on the 1B-element stress configuration (fp32 [131072 x 8192], Student-t(3) entries times a
+log-uniform per-channel spread, 1 % of channels all zero).  Inputs are generated on the host from a
+fixed seed and copied to HBM before the timed region.
+
+Prints one JSON line.  `value` is the metric BASELINE.json names, "quant+dequant GB/s": the
+algorithmic bytes of quantize (4 B read + 1 B written per element) plus dequantize (1 B + 4 B)
+divided by the summed mean durations of those two calls inside the timed steps, measured with HIP
+events on the launch stream.  Every call's own time, GB/s and fraction of the 8 TB/s HBM peak are
+under "kernels"; "roofline" repeats the entry of the call that takes the largest share of a step.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS tokens (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=32768, help="tokens of the workload the CPU oracle is timed on")
+    ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
+                    help="library launch option, e.g. width=16 unroll=2 blocks_per_cu=8 nontemporal=1 exact_div_only=0")
+    return ap.parse_args()
+
+
+def committed_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload.split("[")[0])
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*traffic_bytes_per_launch\[(\w+)\]\s*=\s*([0-9.eE+]+)", line)
+        if m and m.group(1) == kernel:
+            return float(m.group(2))
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus %d refused)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU only: WORLD_SIZE must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_04719_amd import kvq, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    kvq.lib()   # fail loudly now if the HIP library is not built
+
+    optkeys = {"width": kvq.OPT_CODEC_WIDTH, "unroll": kvq.OPT_CODEC_UNROLL,
+               "blocks_per_cu": kvq.OPT_BLOCKS_PER_CU, "nontemporal": kvq.OPT_NONTEMPORAL,
+               "exact_div_only": kvq.OPT_EXACT_DIV_ONLY}
+    for kv in args.opt:
+        k, v = kv.split("=")
+        kvq.kvq_set_option(optkeys[k], int(v))
+    opts = {k: kvq.kvq_get_option(v) for k, v in optkeys.items()}
+
+    c = W.CONFIGS[args.config]
+    N = args.rows if args.rows else c.N
+    batch, D = c.batch, c.D
+    E = batch * N * D
+    t0 = time.time()
+    x_host = W.generate(c, rows=(0, N))
+    t_gen = time.time() - t0
+    dev = torch.device("cuda:0")
+    x = torch.empty(E, dtype=torch.float32, device=dev)
+    x.copy_(torch.from_numpy(x_host.reshape(-1)))
+    scales = torch.empty(batch * D, dtype=torch.float32, device=dev)
+    codes = torch.empty(E, dtype=torch.int8, device=dev)
+    x_hat = torch.empty(E, dtype=torch.float32, device=dev)
+    sumsq = torch.zeros(1, dtype=torch.float64, device=dev)
+    maxabs = torch.zeros(1, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+    names = ["absmax_scales", "quantize", "dequantize", "roundtrip_error"]
+    alg_bytes = {"absmax_scales": 4.0 * E + 4.0 * batch * D,
+                 "quantize": 5.0 * E + 4.0 * batch * D,
+                 "dequantize": 5.0 * E + 4.0 * batch * D,
+                 "roundtrip_error": 8.0 * E}
+
+    def step(events=None):
+        if events:
+            events[0].record(stream)
+        kvq.kvq_absmax_scales(x, scales, batch, N, D, stream=h)
+        if events:
+            events[1].record(stream)
+        kvq.kvq_quantize(x, scales, codes, batch, N, D, stream=h)
+        if events:
+            events[2].record(stream)
+        kvq.kvq_dequantize(codes, scales, x_hat, batch, N, D, stream=h)
+        if events:
+            events[3].record(stream)
+        kvq.kvq_roundtrip_error(x, x_hat, None, None, batch, N, D, sumsq, maxabs, stream=h)
+        if events:
+            events[4].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(ev[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    ms = {n: [ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)] for j, n in enumerate(names)}
+    mean_ms = {n: float(np.mean(v)) for n, v in ms.items()}
+    kernels = {}
+    for n in names:
+        gbps = alg_bytes[n] / (mean_ms[n] * 1e-3) / 1e9
+        kernels[n] = {"ms_mean": round(mean_ms[n], 4), "ms_min": round(float(np.min(ms[n])), 4),
+                      "alg_GB": round(alg_bytes[n] / 1e9, 4), "GBps": round(gbps, 1),
+                      "frac_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+    qd_bytes = alg_bytes["quantize"] + alg_bytes["dequantize"]
+    qd_ms = mean_ms["quantize"] + mean_ms["dequantize"]
+    value = qd_bytes / (qd_ms * 1e-3) / 1e9
+    dominant = max(names, key=lambda n: mean_ms[n])
+    workload = c.name if N == c.N else "%s first %d rows" % (c.name, N)
+    roofline = {"kernel": "kvq_" + dominant, "bound": "hbm",
+                "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": kernels[dominant]["frac_hbm_peak"],
+                "traffic": committed_traffic(dominant, c.name) if N == c.N else None}
+
+    # sanity of what was timed: the run must have produced the statistics of a real round trip
+    ss, mx = float(sumsq.item()), float(maxabs.item())
+    s_max = float(scales.max().item())
+    if not (ss > 0 and 0 < mx <= s_max / 2 * (1 + 2.0 ** -15)):
+        print("round-trip statistics look wrong: sumsq=%r maxabs=%r max scale=%r" % (ss, mx, s_max), file=sys.stderr)
+        sys.exit(1)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(args.cpu_rows, N)
+        xs = np.ascontiguousarray(x_host[0, :rows])
+        t = [time.perf_counter()]
+        s_o = oracle.compute_scales(xs); t.append(time.perf_counter())
+        q_o = oracle.quantize(xs, s_o); t.append(time.perf_counter())
+        xh_o = oracle.dequantize(q_o, s_o); t.append(time.perf_counter())
+        oracle.roundtrip_error(xs, xh_o); t.append(time.perf_counter())
+        e = rows * D
+        cpu_qd = (5.0 * e * 2) / (t[3] - t[1]) / 1e9
+        cpu = {"value": round(cpu_qd, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "first %d of %d tokens of %s (slab 0); quantize + dequantize, same byte count per element "
+                         "as `value`" % (rows, N, c.name),
+               "ms": {"absmax_scales": round((t[1] - t[0]) * 1e3, 1), "quantize": round((t[2] - t[1]) * 1e3, 1),
+                      "dequantize": round((t[3] - t[2]) * 1e3, 1), "roundtrip_error": round((t[4] - t[3]) * 1e3, 1)},
+               "host_cores_available": os.cpu_count()}
+
+    out = {
+        "metric": "quant+dequant GB/s and % of HBM peak on 1B-element fp32 K (1 GPU)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": workload, "batch": batch, "N": N, "D": D, "elements": E, "seed": 0,
+                   "step": "absmax_scales+quantize+dequantize+roundtrip_error(x,x_hat)", "options": opts},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "step_GBps": round(sum(alg_bytes.values()) / (ms_per_step * 1e-3) / 1e9, 1),
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "result": {"l2_error": ss ** 0.5, "max_abs_error": mx},
+        "host_generate_s": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

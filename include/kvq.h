@@ -1,0 +1,157 @@
+/*
+ * kvq.h -- C ABI of the MI355X (gfx950) per-channel symmetric INT8 KV-cache
+ * quantization library (libkvq.so).
+ *
+ * Data model (paper, "Data Structures" and "Per-Channel INT8 Quantization"):
+ * a key or value matrix is token-major, row-major fp32 [N tokens x D channels]
+ * with the channel index contiguous; one fp32 scale per channel (column).  An
+ * optional leading `batch` dimension stacks independent [N x D] slabs
+ * contiguously (slab stride N*D elements); scales are then [batch x D].  A
+ * [B,H,T,d] cache is batch = B*H, N = T, D = d.
+ *
+ * Conventions for every entry point:
+ *  - every data pointer is a DEVICE pointer owned by the caller; the library
+ *    never frees or keeps it.  Scalar results are written to device memory too,
+ *    so no call synchronises: work is enqueued on `stream` (NULL = the default
+ *    stream) and the call returns.
+ *  - any N, D, batch >= 1 is accepted.  Rows whose width or base address do not
+ *    allow 16-byte vector access take a slower generic kernel with identical
+ *    results; nothing is skipped.
+ *  - inputs must be finite (no NaN/Inf); subnormals are honoured (no flush).
+ *  - argument errors are detected on the host before anything is enqueued and
+ *    reported as a negative status with no side effects; a failed HIP call maps
+ *    to KVQ_ERR_HIP.  Input and output buffers must not overlap.
+ *  - kvq_roundtrip_error and kvq_attn_score_error keep a small per-device,
+ *    per-stream workspace (partial sums) that the library allocates on first use;
+ *    two calls in flight on the SAME stream are ordered by the stream, calls on
+ *    different streams use different workspaces.
+ *  - results of kvq_absmax_scales, kvq_quantize, kvq_dequantize are unique bit
+ *    patterns; the error statistics are deterministic for a given shape.
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int kvq_status;
+#define KVQ_OK 0
+#define KVQ_ERR_NULL (-1)     /* a required pointer is NULL                               */
+#define KVQ_ERR_SHAPE (-2)    /* batch, N, D or Q is < 1                                  */
+#define KVQ_ERR_OVERFLOW (-3) /* batch*N*D (or a launch dimension) exceeds what is indexable */
+#define KVQ_ERR_HIP (-4)      /* a HIP runtime call failed; see kvq_last_hip_error()      */
+#define KVQ_ERR_ARG (-5)      /* inconsistent optional arguments                          */
+
+/* Same type as hipStream_t (an opaque pointer); declared here so that callers
+ * need no HIP headers. */
+typedef struct ihipStream_t *kvq_stream_t;
+
+/*
+ * Scale computation -- Eq. (scale)/(scale_compute) and Algorithm "Compute
+ * Scales": scales[b,d] = max_t |x[b,t,d]| / 127 (one IEEE fp32 divide), +0 for
+ * an all-zero channel.
+ *   x      [batch,N,D] fp32, device, read only
+ *   scales [batch,D]   fp32, device, written (also used as reduction scratch
+ *                      while the call runs; needs 4-byte alignment only)
+ */
+kvq_status kvq_absmax_scales(const float *x, float *scales,
+                             int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
+ * Quantization -- Eq. (quantize)/(quant_op) plus the stated clamp:
+ * codes[b,t,d] = clamp(rint(x[b,t,d] / scales[b,d]), -127, 127) with a
+ * correctly rounded fp32 divide and round-half-to-even; 0 where the scale is 0.
+ * Any positive scale is accepted (not only the one kvq_absmax_scales gives).
+ *   x [batch,N,D] fp32, scales [batch,D] fp32: device, read only
+ *   codes [batch,N,D] int8: device, written
+ */
+kvq_status kvq_quantize(const float *x, const float *scales, int8_t *codes,
+                        int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
+ * Dequantization -- Eq. (dequantize)/(dequant_op):
+ * x_hat[b,t,d] = (float)codes[b,t,d] * scales[b,d] (one fp32 multiply).
+ *   codes [batch,N,D] int8, scales [batch,D] fp32: device, read only
+ *   x_hat [batch,N,D] fp32: device, written
+ */
+kvq_status kvq_dequantize(const int8_t *codes, const float *scales, float *x_hat,
+                          int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
+ * Scale computation and quantization in one call (same results as
+ * kvq_absmax_scales followed by kvq_quantize).  Slabs are processed in groups
+ * sized to stay resident in the last-level cache between the two passes, so
+ * x is fetched from HBM once when a group fits.
+ *   x [batch,N,D] fp32 read only; scales [batch,D] fp32 and codes [batch,N,D]
+ *   int8 written.
+ */
+kvq_status kvq_quantize_fused(const float *x, float *scales, int8_t *codes,
+                              int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
+ * Reconstruction error -- Introduction ("Reconstruction error: L2 error and
+ * maximum absolute error") and Evaluation, "Reconstruction Error":
+ *   *sumsq_out  = sum over all elements of (x - x_hat)^2   (fp32 difference,
+ *                 fp64 square and sum; the L2 error is its square root)
+ *   *maxabs_out = max over all elements of |x - x_hat|
+ * Two forms:
+ *   x_hat != NULL: compare x with the fp32 matrix x_hat (codes, scales ignored,
+ *                  may be NULL);
+ *   x_hat == NULL: codes and scales are required and x_hat is recomputed on the
+ *                  fly as (float)code * scale, bit-identical to kvq_dequantize.
+ *   sumsq_out (double, 8-byte aligned) and maxabs_out (float): device, written.
+ */
+kvq_status kvq_roundtrip_error(const float *x, const float *x_hat,
+                               const int8_t *codes, const float *scales,
+                               int64_t batch, int64_t N, int64_t D,
+                               double *sumsq_out, float *maxabs_out, kvq_stream_t stream);
+
+/*
+ * Attention-score error -- Introduction ("mean absolute difference between
+ * attention dot products computed with original and reconstructed keys") and
+ * Evaluation, "Attention Score Error":
+ *   *mean_abs_out = (1/(Q*N)) sum_{j<Q, t<N} | q_j . k_t  -  q_j . k_hat_t |
+ * raw dot products (no 1/sqrt(d), no softmax), accumulated in fp64.
+ *   queries [Q,D] fp32, k [N,D] fp32: device, read only
+ *   k_hat [N,D] fp32, or NULL with codes [N,D] int8 + scales [D] fp32 given
+ *   (k_hat recomputed as in kvq_dequantize)
+ *   mean_abs_out: device double, written.
+ */
+kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
+                                const float *k, const float *k_hat,
+                                const int8_t *codes, const float *scales,
+                                int64_t N, int64_t D,
+                                double *mean_abs_out, kvq_stream_t stream);
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *kvq_status_string(kvq_status status);
+
+/* The hipError_t value of the last failed HIP call on this thread (0 if none). */
+int kvq_last_hip_error(void);
+
+/*
+ * Launch-shape knobs for measurement sweeps; results never depend on them.
+ * Returns KVQ_OK, or KVQ_ERR_ARG for an unknown key or a value outside the
+ * documented range.  Process-wide, not thread-safe against concurrent calls.
+ *   KVQ_OPT_CODEC_WIDTH     elements per lane in quantize/dequantize: 4, 8 or 16
+ *   KVQ_OPT_CODEC_UNROLL    rows in flight per lane: 1, 2 or 4
+ *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit: 1..64
+ *   KVQ_OPT_NONTEMPORAL     0/1: streaming cache hints on loads and stores
+ *   KVQ_OPT_EXACT_DIV_ONLY  0/1: 1 = always use the full IEEE divide sequence
+ *                           (0 = reciprocal multiply, divide only near a tie)
+ */
+#define KVQ_OPT_CODEC_WIDTH 1
+#define KVQ_OPT_CODEC_UNROLL 2
+#define KVQ_OPT_BLOCKS_PER_CU 3
+#define KVQ_OPT_NONTEMPORAL 4
+#define KVQ_OPT_EXACT_DIV_ONLY 5
+kvq_status kvq_set_option(int key, int value);
+int kvq_get_option(int key);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

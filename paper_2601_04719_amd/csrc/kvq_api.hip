@@ -1,0 +1,243 @@
+// C-ABI layer of libkvq.so: argument validation, launch-shape choice, the
+// per-stream workspace.  No arithmetic of the method lives here.
+#include <limits.h>
+
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "kvq_internal.h"
+
+namespace kvq {
+
+static thread_local int g_last_hip_error = 0;
+
+kvq_status hip_failed(hipError_t e) {
+  g_last_hip_error = (int)e;
+  (void)hipGetLastError();  // clear the sticky launch error so later calls start clean
+  return KVQ_ERR_HIP;
+}
+
+Options& options() {
+  static Options o;
+  return o;
+}
+
+DeviceInfo current_device() {
+  static std::mutex mu;
+  static std::map<int, DeviceInfo> cache;
+  DeviceInfo info;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return info;
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find(dev);
+  if (it != cache.end()) return it->second;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return info;
+  info.device = dev;
+  info.cus = cus;
+  cache[dev] = info;
+  return info;
+}
+
+int pick_width(int64_t D, const void* fp32_ptr, const void* int8_ptr, int want) {
+  for (int V = 16; V >= 4; V >>= 1) {
+    if (V > want) continue;
+    if (D % V) continue;
+    // a lane moves V fp32 values as 16-byte vectors and V codes as one V-byte vector
+    if (fp32_ptr && !aligned(fp32_ptr, 16)) continue;
+    if (int8_ptr && !aligned(int8_ptr, (uintptr_t)V)) continue;
+    return V;
+  }
+  return 1;
+}
+
+static int ceil_log2(int64_t v) {
+  int l = 0;
+  while (((int64_t)1 << l) < v) l++;
+  return l;
+}
+
+Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks) {
+  Tiling t;
+  t.V = V;
+  t.groups = (D + V - 1) / V;
+  t.tx_log2 = t.groups >= kBlock ? 8 : ceil_log2(t.groups);
+  const int64_t TX = (int64_t)1 << t.tx_log2;
+  const int64_t TY = kBlock / TX;
+  const int64_t ctiles = (t.groups + TX - 1) / TX;
+  const int64_t step = TY * unroll;  // rows one pass of the workgroup covers
+  const int64_t fixed = batch * ctiles;
+  int64_t want_chunks = (target_blocks + fixed - 1) / fixed;
+  const int64_t max_chunks = (N + step - 1) / step;
+  if (want_chunks > max_chunks) want_chunks = max_chunks;
+  if (want_chunks < 1) want_chunks = 1;
+  int64_t rows = (N + want_chunks - 1) / want_chunks;
+  rows = (rows + step - 1) / step * step;
+  t.rows_per_chunk = rows;
+  const int64_t rchunks = (N + rows - 1) / rows;
+  t.ctiles = (uint32_t)ctiles;
+  t.rchunks = (uint32_t)rchunks;
+  t.items = batch * rchunks * ctiles;
+  return t;
+}
+
+kvq_status get_workspace(hipStream_t stream, Workspace* out) {
+  static std::mutex mu;
+  static std::map<std::pair<int, hipStream_t>, Workspace> table;
+  int dev = -1;
+  KVQ_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  auto key = std::make_pair(dev, stream);
+  auto it = table.find(key);
+  if (it != table.end()) {
+    *out = it->second;
+    return KVQ_OK;
+  }
+  void* p = nullptr;
+  KVQ_HIP(hipMalloc(&p, (size_t)kMaxPartials * (sizeof(double) + sizeof(float))));
+  Workspace w;
+  w.sums = static_cast<double*>(p);
+  w.maxes = reinterpret_cast<float*>(w.sums + kMaxPartials);
+  table[key] = w;
+  *out = w;
+  return KVQ_OK;
+}
+
+// batch, N, D >= 1 and batch*N*D (in bytes of fp32) indexable in int64 / size_t.
+static kvq_status check_shape(int64_t batch, int64_t N, int64_t D) {
+  if (batch < 1 || N < 1 || D < 1) return KVQ_ERR_SHAPE;
+  const int64_t lim = INT64_MAX / 8;  // room for the 4-byte element size and headroom
+  if (N > lim / D) return KVQ_ERR_OVERFLOW;
+  if (batch > lim / (N * D)) return KVQ_ERR_OVERFLOW;
+  if (batch > INT32_MAX / 2 || D > ((int64_t)1 << 40)) return KVQ_ERR_OVERFLOW;
+  if (batch * D > lim) return KVQ_ERR_OVERFLOW;
+  return KVQ_OK;
+}
+
+}  // namespace kvq
+
+using namespace kvq;
+
+extern "C" {
+
+kvq_status kvq_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                             kvq_stream_t stream) {
+  if (!x || !scales) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_absmax_scales(x, scales, batch, N, D, stream);
+}
+
+kvq_status kvq_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                        int64_t D, kvq_stream_t stream) {
+  if (!x || !scales || !codes) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_quantize(x, scales, codes, batch, N, D, stream);
+}
+
+kvq_status kvq_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch, int64_t N,
+                          int64_t D, kvq_stream_t stream) {
+  if (!codes || !scales || !x_hat) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_dequantize(codes, scales, x_hat, batch, N, D, stream);
+}
+
+kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N,
+                              int64_t D, kvq_stream_t stream) {
+  if (!x || !scales || !codes) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  // Groups of whole slabs of at most 64 MiB of fp32: small enough that the
+  // quantize pass of a group finds what its absmax pass just read still in the
+  // 256 MiB memory-side cache.
+  const int64_t slab_bytes = N * D * 4;
+  int64_t per_group = ((int64_t)64 << 20) / slab_bytes;
+  if (per_group < 1) per_group = 1;
+  for (int64_t b0 = 0; b0 < batch; b0 += per_group) {
+    const int64_t nb = batch - b0 < per_group ? batch - b0 : per_group;
+    const float* xg = x + b0 * N * D;
+    float* sg = scales + b0 * D;
+    if (kvq_status s = launch_absmax_scales(xg, sg, nb, N, D, stream)) return s;
+    if (kvq_status s = launch_quantize(xg, sg, codes + b0 * N * D, nb, N, D, stream)) return s;
+  }
+  return KVQ_OK;
+}
+
+kvq_status kvq_roundtrip_error(const float* x, const float* x_hat, const int8_t* codes, const float* scales,
+                               int64_t batch, int64_t N, int64_t D, double* sumsq_out, float* maxabs_out,
+                               kvq_stream_t stream) {
+  if (!x || !sumsq_out || !maxabs_out) return KVQ_ERR_NULL;
+  if (!x_hat && (!codes || !scales)) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (!aligned(sumsq_out, 8) || !aligned(maxabs_out, 4)) return KVQ_ERR_ARG;
+  if (x_hat) return launch_roundtrip_error_dense(x, x_hat, batch * N * D, sumsq_out, maxabs_out, stream);
+  return launch_roundtrip_error_codes(x, codes, scales, batch, N, D, sumsq_out, maxabs_out, stream);
+}
+
+kvq_status kvq_attn_score_error(const float* queries, int64_t Q, const float* k, const float* k_hat,
+                                const int8_t* codes, const float* scales, int64_t N, int64_t D,
+                                double* mean_abs_out, kvq_stream_t stream) {
+  if (!queries || !k || !mean_abs_out) return KVQ_ERR_NULL;
+  if (!k_hat && (!codes || !scales)) return KVQ_ERR_NULL;
+  if (Q < 1) return KVQ_ERR_SHAPE;
+  if (kvq_status s = check_shape(1, N, D)) return s;
+  if (Q > INT32_MAX || Q > (INT64_MAX / 8) / D) return KVQ_ERR_OVERFLOW;
+  if (!aligned(mean_abs_out, 8)) return KVQ_ERR_ARG;
+  return launch_attn_score_error(queries, Q, k, k_hat, codes, scales, N, D, mean_abs_out, stream);
+}
+
+const char* kvq_status_string(kvq_status status) {
+  switch (status) {
+    case KVQ_OK: return "KVQ_OK";
+    case KVQ_ERR_NULL: return "KVQ_ERR_NULL: a required pointer is NULL";
+    case KVQ_ERR_SHAPE: return "KVQ_ERR_SHAPE: batch, N, D and Q must be >= 1";
+    case KVQ_ERR_OVERFLOW: return "KVQ_ERR_OVERFLOW: problem size is not indexable";
+    case KVQ_ERR_HIP: return "KVQ_ERR_HIP: a HIP runtime call failed";
+    case KVQ_ERR_ARG: return "KVQ_ERR_ARG: inconsistent or out-of-range argument";
+    default: return "unknown kvq status";
+  }
+}
+
+int kvq_last_hip_error(void) { return g_last_hip_error; }
+
+kvq_status kvq_set_option(int key, int value) {
+  Options& o = options();
+  switch (key) {
+    case KVQ_OPT_CODEC_WIDTH:
+      if (value != 4 && value != 8 && value != 16) return KVQ_ERR_ARG;
+      o.codec_width = value;
+      return KVQ_OK;
+    case KVQ_OPT_CODEC_UNROLL:
+      if (value != 1 && value != 2 && value != 4) return KVQ_ERR_ARG;
+      o.codec_unroll = value;
+      return KVQ_OK;
+    case KVQ_OPT_BLOCKS_PER_CU:
+      if (value < 1 || value > 64) return KVQ_ERR_ARG;
+      o.blocks_per_cu = value;
+      return KVQ_OK;
+    case KVQ_OPT_NONTEMPORAL:
+      if (value != 0 && value != 1) return KVQ_ERR_ARG;
+      o.nontemporal = value;
+      return KVQ_OK;
+    case KVQ_OPT_EXACT_DIV_ONLY:
+      if (value != 0 && value != 1) return KVQ_ERR_ARG;
+      o.exact_div_only = value;
+      return KVQ_OK;
+    default:
+      return KVQ_ERR_ARG;
+  }
+}
+
+int kvq_get_option(int key) {
+  const Options& o = options();
+  switch (key) {
+    case KVQ_OPT_CODEC_WIDTH: return o.codec_width;
+    case KVQ_OPT_CODEC_UNROLL: return o.codec_unroll;
+    case KVQ_OPT_BLOCKS_PER_CU: return o.blocks_per_cu;
+    case KVQ_OPT_NONTEMPORAL: return o.nontemporal;
+    case KVQ_OPT_EXACT_DIV_ONLY: return o.exact_div_only;
+    default: return INT_MIN;
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Internal declarations shared by the translation units of libkvq.so.
+// Not part of the public ABI (that is include/kvq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvq.h"
+
+namespace kvq {
+
+constexpr int kBlock = 256;  // threads per workgroup everywhere: 4 wavefronts of 64
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// How a [batch, N, D] problem is cut into workgroups.
+//
+// A workgroup is TX x TY lanes (TX * TY = 256, both powers of two).  Lane
+// (tx, ty) owns the V consecutive channels starting at (ctile*TX + tx) * V and
+// walks down the rows r0 + ty, r0 + ty + TY, ... of its row chunk, so whatever
+// is per-channel (scales, running maxima) stays in registers for the whole
+// walk, and a wavefront always touches whole contiguous row segments.
+struct Tiling {
+  int V;                   // channels per lane (1 = generic scalar path)
+  int tx_log2;             // TX = 1 << tx_log2
+  int64_t groups;          // ceil(D / V): lane-columns per row
+  uint32_t ctiles;         // ceil(groups / TX)
+  uint32_t rchunks;        // row chunks per slab
+  int64_t rows_per_chunk;  // multiple of TY * unroll (last chunk may be short)
+  int64_t items;           // batch * rchunks * ctiles = work items
+};
+
+// unroll: rows each lane keeps in flight.  target_blocks: desired number of work
+// items (the row chunking is chosen to reach about that many).
+Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks);
+
+struct Options {
+  int codec_width = 16;
+  int codec_unroll = 2;
+  int blocks_per_cu = 8;
+  int nontemporal = 1;
+  int exact_div_only = 1;
+};
+Options& options();
+
+struct DeviceInfo {
+  int device = -1;
+  int cus = 0;
+};
+// Properties of the current device (cached); cus == 0 on failure.
+DeviceInfo current_device();
+
+// Records a failed HIP call for kvq_last_hip_error(); returns KVQ_ERR_HIP.
+kvq_status hip_failed(hipError_t e);
+#define KVQ_HIP(call)                                   \
+  do {                                                  \
+    hipError_t kvq_e_ = (call);                         \
+    if (kvq_e_ != hipSuccess) return hip_failed(kvq_e_); \
+  } while (0)
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Largest lane width V in {16, 8, 4} (capped by `want`) such that rows of D fp32
+// values / D int8 codes can be accessed with V-wide vectors, else 1.
+int pick_width(int64_t D, const void* fp32_ptr, const void* int8_ptr, int want);
+
+// Per-(device, stream) scratch for the partial results of the error kernels.
+constexpr int kMaxPartials = 8192;
+struct Workspace {
+  double* sums;   // [kMaxPartials]
+  float* maxes;   // [kMaxPartials]
+};
+kvq_status get_workspace(hipStream_t stream, Workspace* out);
+
+// ---- launchers (each validates nothing: the C-ABI layer has done that) ----
+kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                hipStream_t stream);
+kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                           int64_t D, hipStream_t stream);
+kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch,
+                             int64_t N, int64_t D, hipStream_t stream);
+kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int64_t count, double* sumsq_out,
+                                        float* maxabs_out, hipStream_t stream);
+kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, const float* scales,
+                                        int64_t batch, int64_t N, int64_t D, double* sumsq_out,
+                                        float* maxabs_out, hipStream_t stream);
+kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float* k, const float* k_hat,
+                                   const int8_t* codes, const float* scales, int64_t N, int64_t D,
+                                   double* mean_abs_out, hipStream_t stream);
+
+// ---- device helpers ----
+#ifdef __HIPCC__
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* p, T v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// Decomposition of a work-item index into (slab, row chunk, column tile).
+struct Item {
+  int64_t slab;
+  int64_t row0, row1;   // rows [row0, row1) of the slab
+  int64_t group;        // lane-column index of this lane (may be >= groups: inactive)
+  int ty, TY;
+};
+__device__ __forceinline__ Item decode_item(uint32_t item, uint32_t ctiles, uint32_t rchunks,
+                                            int64_t rows_per_chunk, int64_t N, int tx_log2) {
+  Item it;
+  const uint32_t ct = item % ctiles;
+  const uint32_t rest = item / ctiles;
+  const uint32_t rc = rest % rchunks;
+  it.slab = rest / rchunks;
+  const int tid = threadIdx.x;
+  const int tx = tid & ((1 << tx_log2) - 1);
+  it.ty = tid >> tx_log2;
+  it.TY = kBlock >> tx_log2;
+  it.group = (int64_t)ct * (1 << tx_log2) + tx;
+  it.row0 = (int64_t)rc * rows_per_chunk;
+  it.row1 = it.row0 + rows_per_chunk;
+  if (it.row1 > N) it.row1 = N;
+  return it;
+}
+#endif
+
+}  // namespace kvq

@@ -1,0 +1,134 @@
+"""ctypes binding of libkvq.so: same names as include/kvq.h, argument marshalling only.
+
+Arguments may be torch tensors (anything with .data_ptr()), or raw integer
+device addresses.  `stream` is a raw hipStream_t value (for torch:
+torch.cuda.current_stream().cuda_stream) or None for torch's current stream
+when torch is importable and a GPU is present, else the default stream.
+
+There is no CPU fallback: if the shared library is missing, loading raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvq.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_OVERFLOW, ERR_HIP, ERR_ARG = -1, -2, -3, -4, -5
+OPT_CODEC_WIDTH, OPT_CODEC_UNROLL, OPT_BLOCKS_PER_CU, OPT_NONTEMPORAL, OPT_EXACT_DIV_ONLY = 1, 2, 3, 4, 5
+
+EXPORTS = (
+    "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
+    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_status_string",
+    "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
+)
+
+_lib = None
+
+
+class KvqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().kvq_status_string(status).decode()
+        if status == ERR_HIP:
+            msg += " (hipError_t %d)" % lib().kvq_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+def lib():
+    """The loaded shared library (raises OSError with a build hint when it is absent)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("%s not found: build it with `python -m paper_2601_04719_amd.build` "
+                          "(there is no CPU fallback)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.kvq_absmax_scales.argtypes = [p, p, i64, i64, i64, p]
+        L.kvq_quantize.argtypes = [p, p, p, i64, i64, i64, p]
+        L.kvq_dequantize.argtypes = [p, p, p, i64, i64, i64, p]
+        L.kvq_quantize_fused.argtypes = [p, p, p, i64, i64, i64, p]
+        L.kvq_roundtrip_error.argtypes = [p, p, p, p, i64, i64, i64, p, p, p]
+        L.kvq_attn_score_error.argtypes = [p, i64, p, p, p, p, i64, i64, p, p]
+        for name in ("kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
+                     "kvq_roundtrip_error", "kvq_attn_score_error"):
+            getattr(L, name).restype = i32
+        L.kvq_status_string.argtypes = [i32]
+        L.kvq_status_string.restype = ctypes.c_char_p
+        L.kvq_last_hip_error.argtypes = []
+        L.kvq_last_hip_error.restype = i32
+        L.kvq_set_option.argtypes = [i32, i32]
+        L.kvq_set_option.restype = i32
+        L.kvq_get_option.argtypes = [i32]
+        L.kvq_get_option.restype = i32
+        _lib = L
+    return _lib
+
+
+def _addr(a):
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    return a.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream
+    try:
+        import torch
+        if torch.cuda.is_available():
+            return torch.cuda.current_stream().cuda_stream
+    except ImportError:
+        pass
+    return None
+
+
+def _check(status, where):
+    if status != OK:
+        raise KvqError(status, where)
+
+
+def kvq_absmax_scales(x, scales, batch, N, D, stream=None):
+    _check(lib().kvq_absmax_scales(_addr(x), _addr(scales), batch, N, D, _stream(stream)), "kvq_absmax_scales")
+
+
+def kvq_quantize(x, scales, codes, batch, N, D, stream=None):
+    _check(lib().kvq_quantize(_addr(x), _addr(scales), _addr(codes), batch, N, D, _stream(stream)), "kvq_quantize")
+
+
+def kvq_dequantize(codes, scales, x_hat, batch, N, D, stream=None):
+    _check(lib().kvq_dequantize(_addr(codes), _addr(scales), _addr(x_hat), batch, N, D, _stream(stream)),
+           "kvq_dequantize")
+
+
+def kvq_quantize_fused(x, scales, codes, batch, N, D, stream=None):
+    _check(lib().kvq_quantize_fused(_addr(x), _addr(scales), _addr(codes), batch, N, D, _stream(stream)),
+           "kvq_quantize_fused")
+
+
+def kvq_roundtrip_error(x, x_hat, codes, scales, batch, N, D, sumsq_out, maxabs_out, stream=None):
+    _check(lib().kvq_roundtrip_error(_addr(x), _addr(x_hat), _addr(codes), _addr(scales), batch, N, D,
+                                     _addr(sumsq_out), _addr(maxabs_out), _stream(stream)), "kvq_roundtrip_error")
+
+
+def kvq_attn_score_error(queries, Q, k, k_hat, codes, scales, N, D, mean_abs_out, stream=None):
+    _check(lib().kvq_attn_score_error(_addr(queries), Q, _addr(k), _addr(k_hat), _addr(codes), _addr(scales),
+                                      N, D, _addr(mean_abs_out), _stream(stream)), "kvq_attn_score_error")
+
+
+def kvq_status_string(status):
+    return lib().kvq_status_string(status).decode()
+
+
+def kvq_last_hip_error():
+    return lib().kvq_last_hip_error()
+
+
+def kvq_set_option(key, value):
+    _check(lib().kvq_set_option(key, value), "kvq_set_option")
+
+
+def kvq_get_option(key):
+    return lib().kvq_get_option(key)
