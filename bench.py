@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32768, help="tokens of the workload the CPU oracle is timed on")
     ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
-                    help="library launch option, e.g. width=16 unroll=2 blocks_per_cu=8 nontemporal=1 exact_div_only=0")
+                    help="library launch option, e.g. width=4 unroll=2 blocks_per_cu=8 nontemporal=1 block_threads=256 passes_per_block=1")
     return ap.parse_args()
 
 
@@ -73,7 +73,8 @@ def main():
 
     optkeys = {"width": kvq.OPT_CODEC_WIDTH, "unroll": kvq.OPT_CODEC_UNROLL,
                "blocks_per_cu": kvq.OPT_BLOCKS_PER_CU, "nontemporal": kvq.OPT_NONTEMPORAL,
-               "exact_div_only": kvq.OPT_EXACT_DIV_ONLY}
+               "block_threads": kvq.OPT_BLOCK_THREADS, "passes_per_block": kvq.OPT_PASSES_PER_BLOCK,
+               "absmax_unroll": kvq.OPT_ABSMAX_UNROLL, "absmax_passes": kvq.OPT_ABSMAX_PASSES}
     for kv in args.opt:
         k, v = kv.split("=")
         kvq.kvq_set_option(optkeys[k], int(v))

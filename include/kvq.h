@@ -137,17 +137,25 @@ int kvq_last_hip_error(void);
  * Returns KVQ_OK, or KVQ_ERR_ARG for an unknown key or a value outside the
  * documented range.  Process-wide, not thread-safe against concurrent calls.
  *   KVQ_OPT_CODEC_WIDTH     elements per lane in quantize/dequantize: 4, 8 or 16
- *   KVQ_OPT_CODEC_UNROLL    rows in flight per lane: 1, 2 or 4
- *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit: 1..64
+ *   KVQ_OPT_CODEC_UNROLL    rows in flight per lane: 1, 2, 4 or 8; 0 = each kernel's default
+ *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit (used by the reductions,
+ *                           and by quantize/dequantize when PASSES_PER_BLOCK is 0): 1..64
  *   KVQ_OPT_NONTEMPORAL     0/1: streaming cache hints on loads and stores
- *   KVQ_OPT_EXACT_DIV_ONLY  0/1: 1 = always use the full IEEE divide sequence
- *                           (0 = reciprocal multiply, divide only near a tie)
+ *   KVQ_OPT_BLOCK_THREADS   workgroup size of quantize/dequantize: 64, 128, 256 or 512
+ *   KVQ_OPT_PASSES_PER_BLOCK  passes of (rows per workgroup x unroll) one workgroup of
+ *                           quantize/dequantize makes: 1..65536, or 0 = size the grid from
+ *                           BLOCKS_PER_CU instead
+ *   KVQ_OPT_ABSMAX_UNROLL   rows in flight per lane in the absmax reduction: 4, 8 or 16
+ *   KVQ_OPT_ABSMAX_PASSES   as PASSES_PER_BLOCK, for the absmax reduction
  */
 #define KVQ_OPT_CODEC_WIDTH 1
 #define KVQ_OPT_CODEC_UNROLL 2
 #define KVQ_OPT_BLOCKS_PER_CU 3
 #define KVQ_OPT_NONTEMPORAL 4
-#define KVQ_OPT_EXACT_DIV_ONLY 5
+#define KVQ_OPT_BLOCK_THREADS 6
+#define KVQ_OPT_PASSES_PER_BLOCK 7
+#define KVQ_OPT_ABSMAX_UNROLL 8
+#define KVQ_OPT_ABSMAX_PASSES 9
 kvq_status kvq_set_option(int key, int value);
 int kvq_get_option(int key);
 

@@ -9,6 +9,10 @@
 // workgroups with an atomic max on the bit pattern of the (non-negative)
 // float, whose unsigned order equals the float order.  max is associative and
 // commutative, so the result does not depend on the launch shape.
+//
+// Unlike the codec kernels, workgroups here walk long row chunks (about eight
+// workgroups per compute unit): one-shot workgroups of a few rows, each ending
+// in a device-scope read and an atomic per channel, measured 1.5x slower.
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -121,9 +125,14 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options& o = options();
-  constexpr int U = 8;
   const int V = (D % 4 == 0 && aligned(x, 16)) ? 4 : 1;
-  const Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu);
+  const int U = o.absmax_unroll;
+  int passes = o.absmax_passes;
+  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, kBlock, passes);
+  while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
+    passes *= 2;
+    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, kBlock, passes);
+  }
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   const int64_t n_scales = batch * D;
   const int64_t small_blocks = (n_scales + kBlock - 1) / kBlock;
@@ -132,8 +141,14 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
 
   hipLaunchKernelGGL(fill_zero_u32, dim3((uint32_t)small_blocks), dim3(kBlock), 0, stream, bits, n_scales);
   KVQ_HIP(hipGetLastError());
-  kvq_status s = (V == 4) ? launch_absmax_t<4, U>(x, bits, N, D, t, o.nontemporal != 0, stream)
-                          : launch_absmax_t<1, U>(x, bits, N, D, t, false, stream);
+  const bool nt = o.nontemporal != 0;
+  kvq_status s;
+  if (V == 4 && U == 4) s = launch_absmax_t<4, 4>(x, bits, N, D, t, nt, stream);
+  else if (V == 4 && U == 8) s = launch_absmax_t<4, 8>(x, bits, N, D, t, nt, stream);
+  else if (V == 4) s = launch_absmax_t<4, 16>(x, bits, N, D, t, nt, stream);
+  else if (U == 4) s = launch_absmax_t<1, 4>(x, bits, N, D, t, false, stream);
+  else if (U == 8) s = launch_absmax_t<1, 8>(x, bits, N, D, t, false, stream);
+  else s = launch_absmax_t<1, 16>(x, bits, N, D, t, false, stream);
   if (s != KVQ_OK) return s;
   hipLaunchKernelGGL(finalize_scales, dim3((uint32_t)small_blocks), dim3(kBlock), 0, stream, scales, n_scales);
   KVQ_HIP(hipGetLastError());

@@ -59,18 +59,21 @@ static int ceil_log2(int64_t v) {
   return l;
 }
 
-Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks) {
+Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks, int block,
+                   int passes) {
   Tiling t;
   t.V = V;
+  t.block = block;
   t.groups = (D + V - 1) / V;
-  t.tx_log2 = t.groups >= kBlock ? 8 : ceil_log2(t.groups);
+  t.tx_log2 = t.groups >= block ? ceil_log2(block) : ceil_log2(t.groups);
   const int64_t TX = (int64_t)1 << t.tx_log2;
-  const int64_t TY = kBlock / TX;
+  const int64_t TY = block / TX;
   const int64_t ctiles = (t.groups + TX - 1) / TX;
   const int64_t step = TY * unroll;  // rows one pass of the workgroup covers
   const int64_t fixed = batch * ctiles;
-  int64_t want_chunks = (target_blocks + fixed - 1) / fixed;
   const int64_t max_chunks = (N + step - 1) / step;
+  int64_t want_chunks = (target_blocks + fixed - 1) / fixed;
+  if (passes > 0) want_chunks = (max_chunks + passes - 1) / passes;
   if (want_chunks > max_chunks) want_chunks = max_chunks;
   if (want_chunks < 1) want_chunks = 1;
   int64_t rows = (N + want_chunks - 1) / want_chunks;
@@ -208,7 +211,7 @@ kvq_status kvq_set_option(int key, int value) {
       o.codec_width = value;
       return KVQ_OK;
     case KVQ_OPT_CODEC_UNROLL:
-      if (value != 1 && value != 2 && value != 4) return KVQ_ERR_ARG;
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return KVQ_ERR_ARG;
       o.codec_unroll = value;
       return KVQ_OK;
     case KVQ_OPT_BLOCKS_PER_CU:
@@ -219,9 +222,21 @@ kvq_status kvq_set_option(int key, int value) {
       if (value != 0 && value != 1) return KVQ_ERR_ARG;
       o.nontemporal = value;
       return KVQ_OK;
-    case KVQ_OPT_EXACT_DIV_ONLY:
-      if (value != 0 && value != 1) return KVQ_ERR_ARG;
-      o.exact_div_only = value;
+    case KVQ_OPT_BLOCK_THREADS:
+      if (value != 64 && value != 128 && value != 256 && value != 512) return KVQ_ERR_ARG;
+      o.block_threads = value;
+      return KVQ_OK;
+    case KVQ_OPT_PASSES_PER_BLOCK:
+      if (value < 0 || value > 65536) return KVQ_ERR_ARG;
+      o.passes_per_block = value;
+      return KVQ_OK;
+    case KVQ_OPT_ABSMAX_UNROLL:
+      if (value != 4 && value != 8 && value != 16) return KVQ_ERR_ARG;
+      o.absmax_unroll = value;
+      return KVQ_OK;
+    case KVQ_OPT_ABSMAX_PASSES:
+      if (value < 0 || value > 65536) return KVQ_ERR_ARG;
+      o.absmax_passes = value;
       return KVQ_OK;
     default:
       return KVQ_ERR_ARG;
@@ -235,7 +250,10 @@ int kvq_get_option(int key) {
     case KVQ_OPT_CODEC_UNROLL: return o.codec_unroll;
     case KVQ_OPT_BLOCKS_PER_CU: return o.blocks_per_cu;
     case KVQ_OPT_NONTEMPORAL: return o.nontemporal;
-    case KVQ_OPT_EXACT_DIV_ONLY: return o.exact_div_only;
+    case KVQ_OPT_BLOCK_THREADS: return o.block_threads;
+    case KVQ_OPT_PASSES_PER_BLOCK: return o.passes_per_block;
+    case KVQ_OPT_ABSMAX_UNROLL: return o.absmax_unroll;
+    case KVQ_OPT_ABSMAX_PASSES: return o.absmax_passes;
     default: return INT_MIN;
   }
 }

@@ -3,12 +3,20 @@
 //  Eq. (dequantize)/(dequant_op)).
 //
 // Both are pure streams (4 B in + 1 B out, or 1 B in + 4 B out per element),
-// so the layout is chosen for the memory system: a lane owns V adjacent
-// channels (V = 16: four 16-byte fp32 accesses and one 16-byte code access),
-// keeps their scales in registers for its whole walk down the rows, and has
-// U rows in flight.  The paper's fastest variant moves 4 codes per thread and
-// reloads the scales for every element; its shared-memory staging of scales
-// has no counterpart here because nothing is re-read.
+// so everything here is chosen for the memory system, by measurement:
+//  - a lane owns V = 4 adjacent channels: one 16-byte fp32 access and one
+//    4-byte code access, so every memory instruction of a wavefront covers one
+//    contiguous 1 KiB (fp32) or 256 B (codes) segment.  Wider lanes (V = 8, 16:
+//    several 16-byte accesses per lane, 64-byte lane pitch) are kept as
+//    selectable variants; they are slower because each instruction then touches
+//    a quarter of many cache lines.
+//  - workgroups are small and one-shot: each handles U rows of its column tile
+//    and exits, and the hardware dispatcher hands tiles out in address order,
+//    which keeps the set of DRAM pages in use compact.  Persistent grid-stride
+//    loops measured 10-20 % slower.
+//  - the scales of a lane are read once per workgroup (they stay in L2); the
+//    paper's shared-memory staging of scales has no counterpart because nothing
+//    is re-read.
 //
 // Rounding is done without a convert instruction: after the clamp to
 // [-127,127], adding 1.5*2^23 rounds to the nearest integer with ties to even
@@ -22,41 +30,12 @@ namespace kvq {
 
 constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23
 
-// Distance from a .5 tie below which the reciprocal-multiply quotient may round
-// differently from the correctly rounded quotient: |x*r - fl(x/s)| <=
-// 1.5*2^-23 |x/s| < 2^-14 whenever |x/s| < 256, and larger quotients clamp to
-// +-127 either way.
-constexpr float kTieBand = 0.5f - 6.103515625e-05f;  // 0.5 - 2^-14
+// Divisor for a channel: its scale, or +inf for a zero scale (x / inf = +-0 -> code 0).
+__device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
 
-struct LaneScale {
-  float s;  // divisor: the scale, or +inf for a zero scale (x/inf = 0 -> code 0)
-  float r;  // multiplier for the fast path: 1/s, 0 for a zero scale, NaN if 1/s is not safely normal
-};
-
-__device__ __forceinline__ LaneScale prepare_scale(float s) {
-  LaneScale ls;
-  if (s == 0.0f) {
-    ls.s = __builtin_inff();
-    ls.r = 0.0f;
-  } else {
-    ls.s = s;
-    const float a = fabsf(s);
-    ls.r = (a >= 0x1p-100f && a <= 0x1p100f) ? 1.0f / s : __builtin_nanf("");
-  }
-  return ls;
-}
-
-// Returns the float whose low byte is the int8 code of x under scale ls.
-template <bool EXACT>
-__device__ __forceinline__ float code_as_float(float x, const LaneScale& ls) {
-  float y;
-  if constexpr (EXACT) {
-    y = x / ls.s;  // correctly rounded IEEE divide
-  } else {
-    y = x * ls.r;
-    const float f = fabsf(y - rintf(y));
-    if (!(f < kTieBand)) y = x / ls.s;  // near a tie (or unsafe scale): decide with the true quotient
-  }
+// Returns the float whose low byte is the int8 code of x for divisor s.
+__device__ __forceinline__ float code_as_float(float x, float s) {
+  float y = x / s;  // correctly rounded IEEE divide (the full v_div_scale/fmas/fixup sequence)
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
   return y + kMagic;
 }
@@ -89,8 +68,8 @@ __device__ __forceinline__ void set_word(typename CodeVec<V>::type& c, int w, ui
 }
 
 // ------------------------------------------------------------------ quantize
-template <int V, int U, bool NT, bool EXACT>
-__global__ __launch_bounds__(kBlock) void quantize_kernel(const float* __restrict__ x,
+template <int V, int U, bool NT>
+__global__ __launch_bounds__(kMaxBlock) void quantize_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ scales,
                                                           int8_t* __restrict__ codes, int64_t N, int64_t D,
                                                           int tx_log2, uint32_t ctiles, uint32_t rchunks,
@@ -98,11 +77,19 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const float* __restric
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * V;
-  LaneScale ls[V];
+  float ls[V];
   {
     const float* sp = scales + it.slab * D + col;
+    if constexpr (V >= 4) {
 #pragma unroll
-    for (int i = 0; i < V; i++) ls[i] = prepare_scale(sp[i]);
+      for (int w = 0; w < V / 4; w++) {
+        const f32x4 sv = *(reinterpret_cast<const f32x4*>(sp) + w);
+#pragma unroll
+        for (int i = 0; i < 4; i++) ls[4 * w + i] = divisor_of(sv[i]);
+      }
+    } else {
+      ls[0] = divisor_of(sp[0]);
+    }
   }
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
@@ -124,10 +111,10 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const float* __restric
         cvec c;
 #pragma unroll
         for (int w = 0; w < W; w++) {
-          const float a = code_as_float<EXACT>(v[u][w].x, ls[4 * w + 0]);
-          const float b = code_as_float<EXACT>(v[u][w].y, ls[4 * w + 1]);
-          const float cc = code_as_float<EXACT>(v[u][w].z, ls[4 * w + 2]);
-          const float d = code_as_float<EXACT>(v[u][w].w, ls[4 * w + 3]);
+          const float a = code_as_float(v[u][w].x, ls[4 * w + 0]);
+          const float b = code_as_float(v[u][w].y, ls[4 * w + 1]);
+          const float cc = code_as_float(v[u][w].z, ls[4 * w + 2]);
+          const float d = code_as_float(v[u][w].w, ls[4 * w + 3]);
           set_word<V>(c, w, pack4(a, b, cc, d));
         }
         st<NT>(reinterpret_cast<cvec*>(pc + u * step), c);
@@ -138,7 +125,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const float* __restric
     for (; row < it.row1; row += it.TY, px += step, pc += step) do_rows(std::integral_constant<int, 1>{});
   } else {
     for (; row < it.row1; row += it.TY, px += step, pc += step) {
-      const float a = code_as_float<EXACT>(*px, ls[0]);
+      const float a = code_as_float(*px, ls[0]);
       *pc = (int8_t)(__float_as_uint(a) & 0xffu);
     }
   }
@@ -152,7 +139,7 @@ __device__ __forceinline__ float dq(uint32_t word, int b, float s) {
 }
 
 template <int V, int U, bool NT>
-__global__ __launch_bounds__(kBlock) void dequantize_kernel(const int8_t* __restrict__ codes,
+__global__ __launch_bounds__(kMaxBlock) void dequantize_kernel(const int8_t* __restrict__ codes,
                                                             const float* __restrict__ scales,
                                                             float* __restrict__ x_hat, int64_t N, int64_t D,
                                                             int tx_log2, uint32_t ctiles, uint32_t rchunks,
@@ -163,8 +150,16 @@ __global__ __launch_bounds__(kBlock) void dequantize_kernel(const int8_t* __rest
   float s[V];
   {
     const float* sp = scales + it.slab * D + col;
+    if constexpr (V >= 4) {
 #pragma unroll
-    for (int i = 0; i < V; i++) s[i] = sp[i];
+      for (int w = 0; w < V / 4; w++) {
+        const f32x4 sv = *(reinterpret_cast<const f32x4*>(sp) + w);
+#pragma unroll
+        for (int i = 0; i < 4; i++) s[4 * w + i] = sv[i];
+      }
+    } else {
+      s[0] = sp[0];
+    }
   }
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
@@ -203,16 +198,14 @@ __global__ __launch_bounds__(kBlock) void dequantize_kernel(const int8_t* __rest
 // ----------------------------------------------------------------- launchers
 template <int V, int U>
 static kvq_status launch_q(const float* x, const float* scales, int8_t* codes, int64_t N, int64_t D,
-                           const Tiling& t, bool nt, bool exact, hipStream_t stream) {
-  const dim3 grid((uint32_t)t.items), block(kBlock);
-#define KVQ_LAUNCH_Q(NT_, EX_)                                                                           \
-  hipLaunchKernelGGL((quantize_kernel<V, U, NT_, EX_>), grid, block, 0, stream, x, scales, codes, N, D, \
-                     t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups)
-  if (nt && exact) KVQ_LAUNCH_Q(true, true);
-  else if (nt) KVQ_LAUNCH_Q(true, false);
-  else if (exact) KVQ_LAUNCH_Q(false, true);
-  else KVQ_LAUNCH_Q(false, false);
-#undef KVQ_LAUNCH_Q
+                           const Tiling& t, bool nt, hipStream_t stream) {
+  const dim3 grid((uint32_t)t.items), block(t.block);
+  if (nt)
+    hipLaunchKernelGGL((quantize_kernel<V, U, true>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  else
+    hipLaunchKernelGGL((quantize_kernel<V, U, false>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }
@@ -220,7 +213,7 @@ static kvq_status launch_q(const float* x, const float* scales, int8_t* codes, i
 template <int V, int U>
 static kvq_status launch_d(const int8_t* codes, const float* scales, float* x_hat, int64_t N, int64_t D,
                            const Tiling& t, bool nt, hipStream_t stream) {
-  const dim3 grid((uint32_t)t.items), block(kBlock);
+  const dim3 grid((uint32_t)t.items), block(t.block);
   if (nt)
     hipLaunchKernelGGL((dequantize_kernel<V, U, true>), grid, block, 0, stream, codes, scales, x_hat, N, D,
                        t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
@@ -235,40 +228,57 @@ template <typename F>
 static kvq_status dispatch_vu(int V, int U, F&& f) {
 #define KVQ_CASE(V_, U_) \
   if (V == V_ && U == U_) return f(std::integral_constant<int, V_>{}, std::integral_constant<int, U_>{})
-  KVQ_CASE(16, 1); KVQ_CASE(16, 2); KVQ_CASE(16, 4);
+  KVQ_CASE(4, 1); KVQ_CASE(4, 2); KVQ_CASE(4, 4); KVQ_CASE(4, 8);
   KVQ_CASE(8, 1); KVQ_CASE(8, 2); KVQ_CASE(8, 4);
-  KVQ_CASE(4, 1); KVQ_CASE(4, 2); KVQ_CASE(4, 4);
+  KVQ_CASE(16, 1); KVQ_CASE(16, 2); KVQ_CASE(16, 4);
 #undef KVQ_CASE
   return f(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
 }
 
-kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
-                           int64_t D, hipStream_t stream) {
+// Launch shape of a codec kernel.  Vector lanes need the scale rows 16-byte
+// aligned too (batch > 1 with D % 4 == 0 keeps every slab's scales aligned).
+static kvq_status codec_tiling(int64_t batch, int64_t N, int64_t D, const void* fp32_ptr, const void* int8_ptr,
+                               const float* scales, int default_unroll, int* U_out, Tiling* t_out) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options o = options();
-  const int V = pick_width(D, x, codes, o.codec_width);
-  const int U = V == 1 ? 1 : o.codec_unroll;
-  const Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu);
+  int V = pick_width(D, fp32_ptr, int8_ptr, o.codec_width);
+  if (V > 1 && !aligned(scales, 16)) V = 1;
+  int U = o.codec_unroll > 0 ? o.codec_unroll : default_unroll;
+  if (V == 1) U = 1;
+  else if (V > 4 && U > 4) U = 4;
+  int passes = o.passes_per_block;
+  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, o.block_threads, passes);
+  // one-shot workgroups by default; fall back to longer walks only when the grid would not be indexable
+  while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
+    passes *= 2;
+    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, o.block_threads, passes);
+  }
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  return dispatch_vu(V, U, [&](auto v, auto u) {
-    return launch_q<decltype(v)::value, decltype(u)::value>(x, scales, codes, N, D, t, o.nontemporal != 0,
-                                                            o.exact_div_only != 0, stream);
+  *U_out = U;
+  *t_out = t;
+  return KVQ_OK;
+}
+
+kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                           int64_t D, hipStream_t stream) {
+  int U;
+  Tiling t;
+  if (kvq_status s = codec_tiling(batch, N, D, x, codes, scales, 4, &U, &t)) return s;
+  const bool nt = options().nontemporal != 0;
+  return dispatch_vu(t.V, U, [&](auto v, auto u) {
+    return launch_q<decltype(v)::value, decltype(u)::value>(x, scales, codes, N, D, t, nt, stream);
   });
 }
 
 kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch,
                              int64_t N, int64_t D, hipStream_t stream) {
-  const DeviceInfo dev = current_device();
-  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
-  const Options o = options();
-  const int V = pick_width(D, x_hat, codes, o.codec_width);
-  const int U = V == 1 ? 1 : o.codec_unroll;
-  const Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu);
-  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  return dispatch_vu(V, U, [&](auto v, auto u) {
-    return launch_d<decltype(v)::value, decltype(u)::value>(codes, scales, x_hat, N, D, t,
-                                                            o.nontemporal != 0, stream);
+  int U;
+  Tiling t;
+  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, 2, &U, &t)) return s;
+  const bool nt = options().nontemporal != 0;
+  return dispatch_vu(t.V, U, [&](auto v, auto u) {
+    return launch_d<decltype(v)::value, decltype(u)::value>(codes, scales, x_hat, N, D, t, nt, stream);
   });
 }
 

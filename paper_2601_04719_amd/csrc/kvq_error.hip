@@ -76,27 +76,31 @@ __device__ __forceinline__ void err_step(float x, float xh, double& acc, float& 
 
 // ------------------------------------------- reconstruction error, x vs x_hat
 // Flat stream over `count` elements; VEC = 4 needs both pointers 16-byte aligned.
+// Every workgroup owns one contiguous chunk of `chunk` vectors (a multiple of
+// kBlock * U) and walks it front to back with U consecutive 4 KiB tiles of each
+// matrix in flight.
 template <int VEC, int U>
 __global__ __launch_bounds__(kBlock) void roundtrip_dense_kernel(const float* __restrict__ x,
                                                                  const float* __restrict__ xh, int64_t count,
-                                                                 double* __restrict__ sums,
+                                                                 int64_t chunk, double* __restrict__ sums,
                                                                  float* __restrict__ maxes) {
   double acc[VEC];
   float mx = 0.0f;
 #pragma unroll
   for (int i = 0; i < VEC; i++) acc[i] = 0.0;
   const int64_t nvec = count / VEC;
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  int64_t i = (int64_t)blockIdx.x * chunk + threadIdx.x;
+  int64_t end = (int64_t)(blockIdx.x + 1) * chunk;
+  if (end > nvec) end = nvec;
   if constexpr (VEC == 4) {
     const f32x4* xv = reinterpret_cast<const f32x4*>(x);
     const f32x4* hv = reinterpret_cast<const f32x4*>(xh);
-    for (; i + (int64_t)(U - 1) * stride < nvec; i += (int64_t)U * stride) {
+    for (; i + (int64_t)(U - 1) * kBlock < end; i += (int64_t)U * kBlock) {
       f32x4 a[U], b[U];
 #pragma unroll
       for (int u = 0; u < U; u++) {
-        a[u] = ld<true>(xv + i + u * stride);
-        b[u] = ld<true>(hv + i + u * stride);
+        a[u] = ld<true>(xv + i + u * kBlock);
+        b[u] = ld<true>(hv + i + u * kBlock);
       }
 #pragma unroll
       for (int u = 0; u < U; u++) {
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(kBlock) void roundtrip_dense_kernel(const float* __
         err_step(a[u].w, b[u].w, acc[3], mx);
       }
     }
-    for (; i < nvec; i += stride) {
+    for (; i < end; i += kBlock) {
       const f32x4 a = xv[i], b = hv[i];
       err_step(a.x, b.x, acc[0], mx);
       err_step(a.y, b.y, acc[1], mx);
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(kBlock) void roundtrip_dense_kernel(const float* __
       err_step(x[j], xh[j], acc[0], mx);
     }
   } else {
-    for (; i < count; i += stride) err_step(x[i], xh[i], acc[0], mx);
+    for (; i < end; i += kBlock) err_step(x[i], xh[i], acc[0], mx);
   }
   double sum = acc[0];
 #pragma unroll
@@ -217,18 +221,21 @@ kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int6
   if (kvq_status s = get_workspace(stream, &ws)) return s;
   constexpr int U = 4;
   const bool vec = aligned(x, 16) && aligned(x_hat, 16);
-  const int64_t work = vec ? (count + 3) / 4 : count;
-  int64_t blocks = (work + (int64_t)kBlock * U - 1) / ((int64_t)kBlock * U);
-  const int64_t cap = (int64_t)dev.cus * options().blocks_per_cu;
-  if (blocks > cap) blocks = cap;
+  const int64_t work = vec ? count / 4 : count;           // vectors (or elements) to walk
+  const int64_t tile = (int64_t)kBlock * U;
+  int64_t blocks = (int64_t)dev.cus * options().blocks_per_cu;
   if (blocks > kMaxPartials) blocks = kMaxPartials;
+  int64_t chunk = (work + blocks - 1) / blocks;
+  chunk = (chunk + tile - 1) / tile * tile;
+  if (chunk < tile) chunk = tile;
+  blocks = (work + chunk - 1) / chunk;
   if (blocks < 1) blocks = 1;
   if (vec)
     hipLaunchKernelGGL((roundtrip_dense_kernel<4, U>), dim3((uint32_t)blocks), dim3(kBlock), 0, stream, x, x_hat,
-                       count, ws.sums, ws.maxes);
+                       count, chunk, ws.sums, ws.maxes);
   else
     hipLaunchKernelGGL((roundtrip_dense_kernel<1, U>), dim3((uint32_t)blocks), dim3(kBlock), 0, stream, x, x_hat,
-                       count, ws.sums, ws.maxes);
+                       count, chunk, ws.sums, ws.maxes);
   KVQ_HIP(hipGetLastError());
   hipLaunchKernelGGL(fold_partials, dim3(1), dim3(kBlock), 0, stream, ws.sums, ws.maxes, (int)blocks, 1.0,
                      sumsq_out, maxabs_out);
@@ -243,8 +250,10 @@ kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, con
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   Workspace ws;
   if (kvq_status s = get_workspace(stream, &ws)) return s;
-  constexpr int U = 2;
-  const int V = pick_width(D, x, codes, 16);
+  constexpr int U = 4;
+  // 4 channels per lane, as in the codec kernels: every wavefront access is one contiguous segment
+  int V = pick_width(D, x, codes, 4);
+  if (V > 1 && !aligned(scales, 16)) V = 1;
   const Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * options().blocks_per_cu);
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   int64_t blocks = t.items < kMaxPartials ? t.items : kMaxPartials;
@@ -253,9 +262,7 @@ kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, con
   hipLaunchKernelGGL((roundtrip_codes_kernel<V_, U>), grid, block, 0, stream, x, codes, scales, N, D,      \
                      t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, (uint32_t)t.items, ws.sums, \
                      ws.maxes)
-  if (V == 16) KVQ_LAUNCH_RC(16);
-  else if (V == 8) KVQ_LAUNCH_RC(8);
-  else if (V == 4) KVQ_LAUNCH_RC(4);
+  if (V == 4) KVQ_LAUNCH_RC(4);
   else KVQ_LAUNCH_RC(1);
 #undef KVQ_LAUNCH_RC
   KVQ_HIP(hipGetLastError());

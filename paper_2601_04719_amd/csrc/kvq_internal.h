@@ -9,7 +9,8 @@
 
 namespace kvq {
 
-constexpr int kBlock = 256;  // threads per workgroup everywhere: 4 wavefronts of 64
+constexpr int kBlock = 256;     // threads per workgroup of the reduction kernels: 4 wavefronts of 64
+constexpr int kMaxBlock = 512;  // largest workgroup the codec kernels may be launched with
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -18,13 +19,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // How a [batch, N, D] problem is cut into workgroups.
 //
-// A workgroup is TX x TY lanes (TX * TY = 256, both powers of two).  Lane
+// A workgroup is TX x TY lanes (TX * TY = block threads, both powers of two).  Lane
 // (tx, ty) owns the V consecutive channels starting at (ctile*TX + tx) * V and
 // walks down the rows r0 + ty, r0 + ty + TY, ... of its row chunk, so whatever
 // is per-channel (scales, running maxima) stays in registers for the whole
 // walk, and a wavefront always touches whole contiguous row segments.
 struct Tiling {
   int V;                   // channels per lane (1 = generic scalar path)
+  int block;               // threads per workgroup
   int tx_log2;             // TX = 1 << tx_log2
   int64_t groups;          // ceil(D / V): lane-columns per row
   uint32_t ctiles;         // ceil(groups / TX)
@@ -33,16 +35,21 @@ struct Tiling {
   int64_t items;           // batch * rchunks * ctiles = work items
 };
 
-// unroll: rows each lane keeps in flight.  target_blocks: desired number of work
-// items (the row chunking is chosen to reach about that many).
-Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks);
+// unroll: rows each lane keeps in flight.  passes > 0: every workgroup makes that
+// many passes of TY * unroll rows; passes == 0: the row chunking is chosen to give
+// about target_blocks work items.
+Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks,
+                   int block = kBlock, int passes = 0);
 
 struct Options {
-  int codec_width = 16;
-  int codec_unroll = 2;
+  int codec_width = 4;
+  int codec_unroll = 0;  // 0 = per kernel default (quantize 4, dequantize 2)
   int blocks_per_cu = 8;
   int nontemporal = 1;
-  int exact_div_only = 1;
+  int block_threads = 256;
+  int passes_per_block = 1;
+  int absmax_unroll = 8;
+  int absmax_passes = 0;  // 0 = long row chunks sized from blocks_per_cu
 };
 Options& options();
 
@@ -121,7 +128,7 @@ __device__ __forceinline__ Item decode_item(uint32_t item, uint32_t ctiles, uint
   const int tid = threadIdx.x;
   const int tx = tid & ((1 << tx_log2) - 1);
   it.ty = tid >> tx_log2;
-  it.TY = kBlock >> tx_log2;
+  it.TY = (int)blockDim.x >> tx_log2;
   it.group = (int64_t)ct * (1 << tx_log2) + tx;
   it.row0 = (int64_t)rc * rows_per_chunk;
   it.row1 = it.row0 + rows_per_chunk;

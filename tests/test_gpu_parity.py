@@ -255,33 +255,38 @@ def test_unaligned_base_pointers(shape, offset):
 
 
 # ------------------------------------------------------------------ every launch shape, same bits
-def test_all_kernel_variants_give_identical_codes():
+OPT_KEYS = (kvq.OPT_CODEC_WIDTH, kvq.OPT_CODEC_UNROLL, kvq.OPT_BLOCKS_PER_CU, kvq.OPT_NONTEMPORAL,
+            kvq.OPT_BLOCK_THREADS, kvq.OPT_PASSES_PER_BLOCK)
+
+
+def test_all_kernel_variants_give_identical_results():
+    """Cross-variant consistency: lane width, unroll, workgroup size, one-shot or walking
+    workgroups, cache hints -- none of them may change a bit."""
     rng = np.random.default_rng(5)
     x = make_matrix(rng, 2, 515, 272)
     s_ref = oracle.compute_scales(x)
     q_ref = oracle.quantize(x, s_ref)
     xh_ref = oracle.dequantize(q_ref, s_ref)
-    keys = (kvq.OPT_CODEC_WIDTH, kvq.OPT_CODEC_UNROLL, kvq.OPT_BLOCKS_PER_CU, kvq.OPT_NONTEMPORAL,
-            kvq.OPT_EXACT_DIV_ONLY)
-    saved = [kvq.kvq_get_option(k) for k in keys]
+    saved = [kvq.kvq_get_option(k) for k in OPT_KEYS]
     try:
-        for w, u, bpc, nt, ex in itertools.product((4, 8, 16), (1, 2, 4), (1, 8), (0, 1), (0, 1)):
-            for k, v in zip(keys, (w, u, bpc, nt, ex)):
+        combos = list(itertools.product((4, 8, 16), (0, 1, 2, 4, 8), (8,), (0, 1), (256,), (1,)))
+        combos += list(itertools.product((4,), (2,), (1, 8), (1,), (64, 128, 256, 512), (0, 1, 3)))
+        for combo in combos:
+            for k, v in zip(OPT_KEYS, combo):
                 kvq.kvq_set_option(k, v)
             g = Gpu(x)
-            assert_bits_equal(g.absmax_scales(), s_ref, "scales %r" % ((w, u, bpc, nt, ex),))
-            assert_bits_equal(g.quantize(), q_ref, "codes %r" % ((w, u, bpc, nt, ex),))
-            assert_bits_equal(g.dequantize(), xh_ref, "x_hat %r" % ((w, u, bpc, nt, ex),))
+            assert_bits_equal(g.absmax_scales(), s_ref, "scales %r" % (combo,))
+            assert_bits_equal(g.quantize(), q_ref, "codes %r" % (combo,))
+            assert_bits_equal(g.dequantize(), xh_ref, "x_hat %r" % (combo,))
+            assert g.guards_intact(), combo
     finally:
-        for k, v in zip(keys, saved):
+        for k, v in zip(OPT_KEYS, saved):
             kvq.kvq_set_option(k, v)
 
 
 # ------------------------------------------------------------------ numerics corner cases
-@pytest.mark.parametrize("exact_only", [0, 1])
-def test_ties_near_ties_and_clipping_with_given_scales(exact_only):
-    """Quotients on and next to .5 ties, scales that clip, tiny and huge scales: the reciprocal
-    shortcut must fall back to the true divide exactly where it could differ."""
+def test_ties_near_ties_and_clipping_with_given_scales():
+    """Quotients on and next to .5 ties, scales that clip, tiny, huge, zero and negative scales."""
     rng = np.random.default_rng(17)
     N, D = 4096, 64
     s = np.exp(rng.uniform(-3, 3, D)).astype(np.float32)
@@ -294,17 +299,12 @@ def test_ties_near_ties_and_clipping_with_given_scales(exact_only):
     x[1::3] = np.nextafter(x[1::3], np.float32(-np.inf))
     x[:, 0] = (rng.integers(-200, 200, N) * 2.0 ** -141).astype(np.float32)
     x[:, 1] = (rng.standard_normal(N) * 2.0 ** 125).astype(np.float32)
-    old = kvq.kvq_get_option(kvq.OPT_EXACT_DIV_ONLY)
-    try:
-        kvq.kvq_set_option(kvq.OPT_EXACT_DIV_ONLY, exact_only)
-        g = Gpu(x)
-        g.set_scales(s)
-        q_ref = oracle.quantize(x, s)
-        assert_bits_equal(g.quantize()[0], q_ref, "codes near ties")
-        assert_bits_equal(g.dequantize()[0], oracle.dequantize(q_ref, s), "x_hat")
-        assert len(np.unique(q_ref)) == 255
-    finally:
-        kvq.kvq_set_option(kvq.OPT_EXACT_DIV_ONLY, old)
+    g = Gpu(x)
+    g.set_scales(s)
+    q_ref = oracle.quantize(x, s)
+    assert_bits_equal(g.quantize()[0], q_ref, "codes near ties")
+    assert_bits_equal(g.dequantize()[0], oracle.dequantize(q_ref, s), "x_hat")
+    assert len(np.unique(q_ref)) == 255
 
 
 def test_subnormal_inputs_and_scales():
