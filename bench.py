@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS tokens (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32768, help="tokens of the workload the CPU oracle is timed on")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed steps, run one plain fp32 copy of the input (a dispatch of known "
+                         "traffic, 4 B read + 4 B written per element) so that rocprofv3 --pmc counters can be scaled")
     ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
                     help="library launch option, e.g. width=4 unroll=2 blocks_per_cu=8 nontemporal=1 block_threads=256 passes_per_block=1")
     return ap.parse_args()
@@ -133,6 +136,10 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    if args.calibration_copy:
+        x_hat.copy_(x)
+        torch.cuda.synchronize()
+
     ms = {n: [ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)] for j, n in enumerate(names)}
     mean_ms = {n: float(np.mean(v)) for n, v in ms.items()}
     kernels = {}
@@ -140,7 +147,8 @@ def main():
         gbps = alg_bytes[n] / (mean_ms[n] * 1e-3) / 1e9
         kernels[n] = {"ms_mean": round(mean_ms[n], 4), "ms_min": round(float(np.min(ms[n])), 4),
                       "alg_GB": round(alg_bytes[n] / 1e9, 4), "GBps": round(gbps, 1),
-                      "frac_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+                      "frac_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                      "traffic": committed_traffic(n, c.name) if N == c.N else None}
     qd_bytes = alg_bytes["quantize"] + alg_bytes["dequantize"]
     qd_ms = mean_ms["quantize"] + mean_ms["dequantize"]
     value = qd_bytes / (qd_ms * 1e-3) / 1e9
@@ -149,7 +157,7 @@ def main():
     roofline = {"kernel": "kvq_" + dominant, "bound": "hbm",
                 "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": kernels[dominant]["frac_hbm_peak"],
-                "traffic": committed_traffic(dominant, c.name) if N == c.N else None}
+                "traffic": kernels[dominant]["traffic"]}
 
     # sanity of what was timed: the run must have produced the statistics of a real round trip
     ss, mx = float(sumsq.item()), float(maxabs.item())
