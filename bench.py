@@ -77,7 +77,8 @@ def main():
     optkeys = {"width": kvq.OPT_CODEC_WIDTH, "unroll": kvq.OPT_CODEC_UNROLL,
                "blocks_per_cu": kvq.OPT_BLOCKS_PER_CU, "nontemporal": kvq.OPT_NONTEMPORAL,
                "block_threads": kvq.OPT_BLOCK_THREADS, "passes_per_block": kvq.OPT_PASSES_PER_BLOCK,
-               "absmax_unroll": kvq.OPT_ABSMAX_UNROLL, "absmax_passes": kvq.OPT_ABSMAX_PASSES}
+               "absmax_unroll": kvq.OPT_ABSMAX_UNROLL, "absmax_passes": kvq.OPT_ABSMAX_PASSES,
+               "absmax_span": kvq.OPT_ABSMAX_SPAN, "absmax_blocks_per_cu": kvq.OPT_ABSMAX_BLOCKS_PER_CU}
     for kv in args.opt:
         k, v = kv.split("=")
         kvq.kvq_set_option(optkeys[k], int(v))

@@ -138,7 +138,7 @@ int kvq_last_hip_error(void);
  * documented range.  Process-wide, not thread-safe against concurrent calls.
  *   KVQ_OPT_CODEC_WIDTH     elements per lane in quantize/dequantize: 4, 8 or 16
  *   KVQ_OPT_CODEC_UNROLL    rows in flight per lane: 1, 2, 4 or 8; 0 = each kernel's default
- *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit (used by the reductions,
+ *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit (used by the error reductions,
  *                           and by quantize/dequantize when PASSES_PER_BLOCK is 0): 1..64
  *   KVQ_OPT_NONTEMPORAL     0/1: streaming cache hints on loads and stores
  *   KVQ_OPT_BLOCK_THREADS   workgroup size of quantize/dequantize: 64, 128, 256 or 512
@@ -147,6 +147,10 @@ int kvq_last_hip_error(void);
  *                           BLOCKS_PER_CU instead
  *   KVQ_OPT_ABSMAX_UNROLL   rows in flight per lane in the absmax reduction: 4, 8 or 16
  *   KVQ_OPT_ABSMAX_PASSES   as PASSES_PER_BLOCK, for the absmax reduction
+ *   KVQ_OPT_ABSMAX_SPAN     16-byte column groups one lane of the absmax reduction owns per
+ *                           row (1, 2, 4 or 8; capped so that a workgroup spans at most a row)
+ *   KVQ_OPT_ABSMAX_BLOCKS_PER_CU  target workgroups per compute unit of the absmax reduction
+ *                           when ABSMAX_PASSES is 0: 1..64
  */
 #define KVQ_OPT_CODEC_WIDTH 1
 #define KVQ_OPT_CODEC_UNROLL 2
@@ -156,6 +160,8 @@ int kvq_last_hip_error(void);
 #define KVQ_OPT_PASSES_PER_BLOCK 7
 #define KVQ_OPT_ABSMAX_UNROLL 8
 #define KVQ_OPT_ABSMAX_PASSES 9
+#define KVQ_OPT_ABSMAX_SPAN 10
+#define KVQ_OPT_ABSMAX_BLOCKS_PER_CU 11
 kvq_status kvq_set_option(int key, int value);
 int kvq_get_option(int key);
 

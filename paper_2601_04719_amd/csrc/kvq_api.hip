@@ -238,6 +238,14 @@ kvq_status kvq_set_option(int key, int value) {
       if (value < 0 || value > 65536) return KVQ_ERR_ARG;
       o.absmax_passes = value;
       return KVQ_OK;
+    case KVQ_OPT_ABSMAX_BLOCKS_PER_CU:
+      if (value < 1 || value > 64) return KVQ_ERR_ARG;
+      o.absmax_blocks_per_cu = value;
+      return KVQ_OK;
+    case KVQ_OPT_ABSMAX_SPAN:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return KVQ_ERR_ARG;
+      o.absmax_span = value;
+      return KVQ_OK;
     default:
       return KVQ_ERR_ARG;
   }
@@ -254,6 +262,8 @@ int kvq_get_option(int key) {
     case KVQ_OPT_PASSES_PER_BLOCK: return o.passes_per_block;
     case KVQ_OPT_ABSMAX_UNROLL: return o.absmax_unroll;
     case KVQ_OPT_ABSMAX_PASSES: return o.absmax_passes;
+    case KVQ_OPT_ABSMAX_SPAN: return o.absmax_span;
+    case KVQ_OPT_ABSMAX_BLOCKS_PER_CU: return o.absmax_blocks_per_cu;
     default: return INT_MIN;
   }
 }

@@ -49,6 +49,8 @@ struct Options {
   int block_threads = 256;
   int passes_per_block = 1;
   int absmax_unroll = 8;
+  int absmax_blocks_per_cu = 1;
+  int absmax_span = 8;    // column groups per lane (1, 2, 4, 8), capped by the row width
   int absmax_passes = 0;  // 0 = long row chunks sized from blocks_per_cu
 };
 Options& options();

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libkvq.so")
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_OVERFLOW, ERR_HIP, ERR_ARG = -1, -2, -3, -4, -5
 OPT_CODEC_WIDTH, OPT_CODEC_UNROLL, OPT_BLOCKS_PER_CU, OPT_NONTEMPORAL = 1, 2, 3, 4
-OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES = 6, 7, 8, 9
+OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES, OPT_ABSMAX_SPAN = 6, 7, 8, 9, 10
+OPT_ABSMAX_BLOCKS_PER_CU = 11
 
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
