@@ -82,9 +82,10 @@ kvq_status kvq_dequantize(const int8_t *codes, const float *scales, float *x_hat
 
 /*
  * Scale computation and quantization in one call (same results as
- * kvq_absmax_scales followed by kvq_quantize).  Slabs are processed in groups
- * sized to stay resident in the last-level cache between the two passes, so
- * x is fetched from HBM once when a group fits.
+ * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
+ * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in
+ * one workgroup's registers: one launch, x fetched from HBM once.  Larger
+ * slabs run the two passes back to back.
  *   x [batch,N,D] fp32 read only; scales [batch,D] fp32 and codes [batch,N,D]
  *   int8 written.
  */

@@ -150,20 +150,12 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;
   if (kvq_status s = check_shape(batch, N, D)) return s;
-  // Groups of whole slabs of at most 64 MiB of fp32: small enough that the
-  // quantize pass of a group finds what its absmax pass just read still in the
-  // 256 MiB memory-side cache.
-  const int64_t slab_bytes = N * D * 4;
-  int64_t per_group = ((int64_t)64 << 20) / slab_bytes;
-  if (per_group < 1) per_group = 1;
-  for (int64_t b0 = 0; b0 < batch; b0 += per_group) {
-    const int64_t nb = batch - b0 < per_group ? batch - b0 : per_group;
-    const float* xg = x + b0 * N * D;
-    float* sg = scales + b0 * D;
-    if (kvq_status s = launch_absmax_scales(xg, sg, nb, N, D, stream)) return s;
-    if (kvq_status s = launch_quantize(xg, sg, codes + b0 * N * D, nb, N, D, stream)) return s;
-  }
-  return KVQ_OK;
+  // A slab that fits one workgroup's registers is read once; anything larger needs every row of a
+  // column before its first code can be written, i.e. two passes over x.  (Splitting the batch into
+  // groups small enough for the 256 MiB memory-side cache was measured and gave no reuse.)
+  if (fused_slab_applicable(x, scales, codes, N, D)) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
+  if (kvq_status s = launch_absmax_scales(x, scales, batch, N, D, stream)) return s;
+  return launch_quantize(x, scales, codes, batch, N, D, stream);
 }
 
 kvq_status kvq_roundtrip_error(const float* x, const float* x_hat, const int8_t* codes, const float* scales,

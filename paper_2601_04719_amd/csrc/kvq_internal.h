@@ -91,6 +91,10 @@ kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, i
                            int64_t D, hipStream_t stream);
 kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch,
                              int64_t N, int64_t D, hipStream_t stream);
+// One-pass absmax + quantize for slabs that fit one workgroup's registers.
+bool fused_slab_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D);
+kvq_status launch_fused_slab(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
+                             hipStream_t stream);
 kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int64_t count, double* sumsq_out,
                                         float* maxabs_out, hipStream_t stream);
 kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, const float* scales,

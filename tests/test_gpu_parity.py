@@ -128,6 +128,12 @@ def full_round_trip_check(x_np, queries=None, offset=0, tag=""):
         for from_codes in (False, True):
             assert g.attn_score_error(queries, from_codes) == pytest.approx(a_ref, rel=REL, abs=0), tag + " attn"
     assert g.guards_intact(), tag + " wrote outside its buffers"
+    # the one-call variant (single pass for small slabs, two passes otherwise) gives the same bits
+    g2 = Gpu(x_np, offset=offset)
+    s_f, q_f = g2.quantize_fused()
+    assert_bits_equal(s_f, s_ref, tag + " fused scales")
+    assert_bits_equal(q_f, q_ref, tag + " fused codes")
+    assert g2.guards_intact(), tag + " fused wrote outside its buffers"
     return g
 
 
@@ -252,6 +258,24 @@ def test_unaligned_base_pointers(shape, offset):
     x = make_matrix(rng, *shape)
     qs = rng.standard_normal((3, shape[2])).astype(np.float32) if shape[0] == 1 else None
     full_round_trip_check(x, qs, offset=offset, tag="offset %d" % offset)
+
+
+FUSED_SHAPES = [(7, 512, 128), (3, 1000, 64), (2, 16, 4096), (5, 17, 20), (1, 16384, 4), (1, 16385, 4),
+                (4, 2048, 32), (9, 1, 8), (2, 513, 128), (1, 65, 1024), (300, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_single_pass_fused_slabs(shape):
+    """Slabs at, below and just above what one workgroup's registers hold."""
+    rng = np.random.default_rng(sum(shape))
+    x = make_matrix(rng, *shape)
+    s_ref = oracle.compute_scales(x)
+    q_ref = oracle.quantize(x, s_ref)
+    g = Gpu(x)
+    s_f, q_f = g.quantize_fused()
+    assert_bits_equal(s_f, s_ref, "fused scales")
+    assert_bits_equal(q_f, q_ref, "fused codes")
+    assert g.guards_intact()
 
 
 # ------------------------------------------------------------------ every launch shape, same bits
