@@ -30,7 +30,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=15)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS tokens (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -167,6 +167,23 @@ def main():
         print("round-trip statistics look wrong: sumsq=%r maxabs=%r max scale=%r" % (ss, mx, s_max), file=sys.stderr)
         sys.exit(1)
 
+    # measured no-math streaming ceilings of this GPU for the same traffic patterns (context for `frac`)
+    def probe(mode, nbytes):
+        f = lambda: kvq.kvq_probe_stream(mode, x, x_hat, codes, codes, scales, batch, N, D, stream=h)
+        for _ in range(5):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(10):
+            f()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return round(nbytes / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9, 1)
+    ceilings = {"read_only": probe(0, 4.0 * E), "write_only": probe(1, 4.0 * E),
+                "read4_write1": probe(2, 5.0 * E), "read1_write4": probe(3, 5.0 * E), "unit": "GB/s",
+                "note": "kvq_probe_stream: flat one-shot read / write kernels, and the production quantize / "
+                        "dequantize kernels with their arithmetic compiled out"}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -197,6 +214,7 @@ def main():
         "step_GBps": round(sum(alg_bytes.values()) / (ms_per_step * 1e-3) / 1e9, 1),
         "kernels": kernels,
         "roofline": roofline,
+        "measured_stream_ceilings": ceilings,
         "cpu_baseline": cpu,
         "result": {"l2_error": ss ** 0.5, "max_abs_error": mx},
         "host_generate_s": round(t_gen, 1),

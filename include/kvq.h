@@ -93,6 +93,23 @@ kvq_status kvq_quantize_fused(const float *x, float *scales, int8_t *codes,
                               int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
 
 /*
+ * Quantization by one of the four kernel designs the paper compares ("GPU
+ * Kernel Variants": naive = one lane per element, tiled = scales staged in
+ * LDS, coarsened = one lane per channel walking the tokens, vectorized = four
+ * channels per lane), re-written for gfx950 as ablation points, or by the
+ * production kernel.  Same arguments and bit-identical codes as kvq_quantize.
+ * KVQ_VARIANT_VECTORIZED needs D % 4 == 0 and 16-byte aligned x and scales
+ * (KVQ_ERR_ARG otherwise; the paper's version skips a ragged tail instead).
+ */
+#define KVQ_VARIANT_PRODUCTION 0
+#define KVQ_VARIANT_NAIVE 1
+#define KVQ_VARIANT_TILED 2
+#define KVQ_VARIANT_COARSENED 3
+#define KVQ_VARIANT_VECTORIZED 4
+kvq_status kvq_quantize_variant(int variant, const float *x, const float *scales, int8_t *codes,
+                                int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
  * Reconstruction error -- Introduction ("Reconstruction error: L2 error and
  * maximum absolute error") and Evaluation, "Reconstruction Error":
  *   *sumsq_out  = sum over all elements of (x - x_hat)^2   (fp32 difference,
@@ -127,6 +144,22 @@ kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
                                 int64_t N, int64_t D,
                                 double *mean_abs_out, kvq_stream_t stream);
 
+/*
+ * Measurement aid: no-math streaming kernels, to find what this GPU's memory
+ * system sustains for the library's traffic patterns over a [batch,N,D] problem.
+ *   mode 0: read the fp32 matrix src_f32                  (4 B/element; flat one-shot kernel)
+ *   mode 1: write the fp32 matrix dst_f32                 (4 B/element; flat one-shot kernel)
+ *   mode 2: the quantize kernel with its arithmetic compiled out: reads src_f32 and
+ *           scales, writes dst_i8                         (5 B/element)
+ *   mode 3: the dequantize kernel likewise: reads src_i8 and scales, writes dst_f32
+ * Pointers a mode does not use may be NULL.  D % 4 == 0; fp32 pointers 16-byte and
+ * byte pointers 4-byte aligned (KVQ_ERR_ARG otherwise, also when launch options
+ * select another kernel shape than the default).  What is written is meaningless.
+ */
+kvq_status kvq_probe_stream(int mode, const float *src_f32, float *dst_f32,
+                            const int8_t *src_i8, int8_t *dst_i8, const float *scales,
+                            int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char *kvq_status_string(kvq_status status);
 
@@ -142,7 +175,8 @@ int kvq_last_hip_error(void);
  *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit (used by the error reductions,
  *                           and by quantize/dequantize when PASSES_PER_BLOCK is 0): 1..64
  *   KVQ_OPT_NONTEMPORAL     0/1: streaming cache hints on loads and stores
- *   KVQ_OPT_BLOCK_THREADS   workgroup size of quantize/dequantize: 64, 128, 256 or 512
+ *   KVQ_OPT_BLOCK_THREADS   workgroup size of quantize/dequantize: 64, 128, 256 or 512;
+ *                           0 = each kernel's default
  *   KVQ_OPT_PASSES_PER_BLOCK  passes of (rows per workgroup x unroll) one workgroup of
  *                           quantize/dequantize makes: 1..65536, or 0 = size the grid from
  *                           BLOCKS_PER_CU instead

@@ -158,6 +158,15 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
   return launch_quantize(x, scales, codes, batch, N, D, stream);
 }
 
+kvq_status kvq_quantize_variant(int variant, const float* x, const float* scales, int8_t* codes, int64_t batch,
+                                int64_t N, int64_t D, kvq_stream_t stream) {
+  if (!x || !scales || !codes) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (variant == KVQ_VARIANT_PRODUCTION) return launch_quantize(x, scales, codes, batch, N, D, stream);
+  if (variant < KVQ_VARIANT_PRODUCTION || variant > KVQ_VARIANT_VECTORIZED) return KVQ_ERR_ARG;
+  return launch_quantize_variant(variant, x, scales, codes, batch, N, D, stream);
+}
+
 kvq_status kvq_roundtrip_error(const float* x, const float* x_hat, const int8_t* codes, const float* scales,
                                int64_t batch, int64_t N, int64_t D, double* sumsq_out, float* maxabs_out,
                                kvq_stream_t stream) {
@@ -215,7 +224,7 @@ kvq_status kvq_set_option(int key, int value) {
       o.nontemporal = value;
       return KVQ_OK;
     case KVQ_OPT_BLOCK_THREADS:
-      if (value != 64 && value != 128 && value != 256 && value != 512) return KVQ_ERR_ARG;
+      if (value != 0 && value != 64 && value != 128 && value != 256 && value != 512) return KVQ_ERR_ARG;
       o.block_threads = value;
       return KVQ_OK;
     case KVQ_OPT_PASSES_PER_BLOCK:

@@ -13,7 +13,8 @@
 //  - workgroups are small and one-shot: each handles U rows of its column tile
 //    and exits, and the hardware dispatcher hands tiles out in address order,
 //    which keeps the set of DRAM pages in use compact.  Persistent grid-stride
-//    loops measured 10-20 % slower.
+//    loops measured 10-20 % slower.  Defaults from interleaved sweeps over
+//    D = 1024..8192: quantize 512 lanes x 4 rows, dequantize 256 lanes x 2 rows.
 //  - the scales of a lane are read once per workgroup (they stay in L2); the
 //    paper's shared-memory staging of scales has no counterpart because nothing
 //    is re-read.
@@ -68,7 +69,8 @@ __device__ __forceinline__ void set_word(typename CodeVec<V>::type& c, int w, ui
 }
 
 // ------------------------------------------------------------------ quantize
-template <int V, int U, bool NT>
+// MATH = false gives the no-math streaming probe: same loads and stores, codes replaced by a bit mix.
+template <int V, int U, bool NT, bool MATH = true>
 __global__ __launch_bounds__(kMaxBlock) void quantize_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ scales,
                                                           int8_t* __restrict__ codes, int64_t N, int64_t D,
@@ -111,11 +113,16 @@ __global__ __launch_bounds__(kMaxBlock) void quantize_kernel(const float* __rest
         cvec c;
 #pragma unroll
         for (int w = 0; w < W; w++) {
-          const float a = code_as_float(v[u][w].x, ls[4 * w + 0]);
-          const float b = code_as_float(v[u][w].y, ls[4 * w + 1]);
-          const float cc = code_as_float(v[u][w].z, ls[4 * w + 2]);
-          const float d = code_as_float(v[u][w].w, ls[4 * w + 3]);
-          set_word<V>(c, w, pack4(a, b, cc, d));
+          if constexpr (MATH) {
+            const float a = code_as_float(v[u][w].x, ls[4 * w + 0]);
+            const float b = code_as_float(v[u][w].y, ls[4 * w + 1]);
+            const float cc = code_as_float(v[u][w].z, ls[4 * w + 2]);
+            const float d = code_as_float(v[u][w].w, ls[4 * w + 3]);
+            set_word<V>(c, w, pack4(a, b, cc, d));
+          } else {
+            set_word<V>(c, w, __float_as_uint(v[u][w].x) ^ __float_as_uint(v[u][w].y) ^ __float_as_uint(v[u][w].z) ^
+                                  __float_as_uint(v[u][w].w) ^ __float_as_uint(ls[4 * w]));
+          }
         }
         st<NT>(reinterpret_cast<cvec*>(pc + u * step), c);
       }
@@ -138,7 +145,7 @@ __device__ __forceinline__ float dq(uint32_t word, int b, float s) {
   return (float)q * s;
 }
 
-template <int V, int U, bool NT>
+template <int V, int U, bool NT, bool MATH = true>
 __global__ __launch_bounds__(kMaxBlock) void dequantize_kernel(const int8_t* __restrict__ codes,
                                                             const float* __restrict__ scales,
                                                             float* __restrict__ x_hat, int64_t N, int64_t D,
@@ -180,10 +187,17 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_kernel(const int8_t* __r
         for (int w = 0; w < W; w++) {
           const uint32_t word = word_of<V>(c[u], w);
           f32x4 o;
-          o.x = dq(word, 0, s[4 * w + 0]);
-          o.y = dq(word, 1, s[4 * w + 1]);
-          o.z = dq(word, 2, s[4 * w + 2]);
-          o.w = dq(word, 3, s[4 * w + 3]);
+          if constexpr (MATH) {
+            o.x = dq(word, 0, s[4 * w + 0]);
+            o.y = dq(word, 1, s[4 * w + 1]);
+            o.z = dq(word, 2, s[4 * w + 2]);
+            o.w = dq(word, 3, s[4 * w + 3]);
+          } else {
+            o.x = __uint_as_float(word);
+            o.y = s[4 * w + 1];
+            o.z = __uint_as_float(word >> 8);
+            o.w = s[4 * w + 3];
+          }
           st<NT>(reinterpret_cast<f32x4*>(px + u * step) + w, o);
         }
     };
@@ -238,7 +252,8 @@ static kvq_status dispatch_vu(int V, int U, F&& f) {
 // Launch shape of a codec kernel.  Vector lanes need the scale rows 16-byte
 // aligned too (batch > 1 with D % 4 == 0 keeps every slab's scales aligned).
 static kvq_status codec_tiling(int64_t batch, int64_t N, int64_t D, const void* fp32_ptr, const void* int8_ptr,
-                               const float* scales, int default_unroll, int* U_out, Tiling* t_out) {
+                               const float* scales, int default_unroll, int default_block, int* U_out,
+                               Tiling* t_out) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options o = options();
@@ -248,11 +263,12 @@ static kvq_status codec_tiling(int64_t batch, int64_t N, int64_t D, const void* 
   if (V == 1) U = 1;
   else if (V > 4 && U > 4) U = 4;
   int passes = o.passes_per_block;
-  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, o.block_threads, passes);
+  const int block = o.block_threads > 0 ? o.block_threads : default_block;
+  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
   // one-shot workgroups by default; fall back to longer walks only when the grid would not be indexable
   while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
     passes *= 2;
-    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, o.block_threads, passes);
+    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
   }
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   *U_out = U;
@@ -264,7 +280,7 @@ kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, i
                            int64_t D, hipStream_t stream) {
   int U;
   Tiling t;
-  if (kvq_status s = codec_tiling(batch, N, D, x, codes, scales, 4, &U, &t)) return s;
+  if (kvq_status s = codec_tiling(batch, N, D, x, codes, scales, 4, 512, &U, &t)) return s;
   const bool nt = options().nontemporal != 0;
   return dispatch_vu(t.V, U, [&](auto v, auto u) {
     return launch_q<decltype(v)::value, decltype(u)::value>(x, scales, codes, N, D, t, nt, stream);
@@ -275,11 +291,33 @@ kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_
                              int64_t N, int64_t D, hipStream_t stream) {
   int U;
   Tiling t;
-  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, 2, &U, &t)) return s;
+  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, 2, 256, &U, &t)) return s;
   const bool nt = options().nontemporal != 0;
   return dispatch_vu(t.V, U, [&](auto v, auto u) {
     return launch_d<decltype(v)::value, decltype(u)::value>(codes, scales, x_hat, N, D, t, nt, stream);
   });
+}
+
+// No-math probes with the production launch shape (default options): mode 2 = the quantize traffic
+// (4 B in, 1 B out), mode 3 = the dequantize traffic (1 B in, 4 B out).
+kvq_status launch_probe_codec(int mode, const float* src_f32, float* dst_f32, const int8_t* src_i8,
+                              int8_t* dst_i8, const float* scales, int64_t batch, int64_t N, int64_t D,
+                              hipStream_t stream) {
+  int U;
+  Tiling t;
+  if (mode == 2) {
+    if (kvq_status s = codec_tiling(batch, N, D, src_f32, dst_i8, scales, 4, 512, &U, &t)) return s;
+    if (t.V != 4 || U != 4) return KVQ_ERR_ARG;
+    hipLaunchKernelGGL((quantize_kernel<4, 4, true, false>), dim3((uint32_t)t.items), dim3(t.block), 0, stream,
+                       src_f32, scales, dst_i8, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  } else {
+    if (kvq_status s = codec_tiling(batch, N, D, dst_f32, src_i8, scales, 2, 256, &U, &t)) return s;
+    if (t.V != 4 || U != 2) return KVQ_ERR_ARG;
+    hipLaunchKernelGGL((dequantize_kernel<4, 2, true, false>), dim3((uint32_t)t.items), dim3(t.block), 0, stream,
+                       src_i8, scales, dst_f32, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  }
+  KVQ_HIP(hipGetLastError());
+  return KVQ_OK;
 }
 
 }  // namespace kvq

@@ -46,7 +46,7 @@ struct Options {
   int codec_unroll = 0;  // 0 = per kernel default (quantize 4, dequantize 2)
   int blocks_per_cu = 8;
   int nontemporal = 1;
-  int block_threads = 256;
+  int block_threads = 0;  // 0 = per kernel default (quantize 512, dequantize 256)
   int passes_per_block = 1;
   int absmax_unroll = 8;
   int absmax_blocks_per_cu = 1;
@@ -95,6 +95,11 @@ kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_
 bool fused_slab_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D);
 kvq_status launch_fused_slab(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
                              hipStream_t stream);
+kvq_status launch_quantize_variant(int variant, const float* x, const float* scales, int8_t* codes,
+                                   int64_t batch, int64_t N, int64_t D, hipStream_t stream);
+kvq_status launch_probe_codec(int mode, const float* src_f32, float* dst_f32, const int8_t* src_i8,
+                              int8_t* dst_i8, const float* scales, int64_t batch, int64_t N, int64_t D,
+                              hipStream_t stream);
 kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int64_t count, double* sumsq_out,
                                         float* maxabs_out, hipStream_t stream);
 kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, const float* scales,

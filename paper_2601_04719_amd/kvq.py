@@ -20,8 +20,8 @@ OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES, O
 OPT_ABSMAX_BLOCKS_PER_CU = 11
 
 EXPORTS = (
-    "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
-    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_status_string",
+    "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
+    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
 )
 
@@ -50,6 +50,10 @@ def lib():
         L.kvq_quantize.argtypes = [p, p, p, i64, i64, i64, p]
         L.kvq_dequantize.argtypes = [p, p, p, i64, i64, i64, p]
         L.kvq_quantize_fused.argtypes = [p, p, p, i64, i64, i64, p]
+        L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
+        L.kvq_quantize_variant.restype = i32
+        L.kvq_probe_stream.argtypes = [i32, p, p, p, p, p, i64, i64, i64, p]
+        L.kvq_probe_stream.restype = i32
         L.kvq_roundtrip_error.argtypes = [p, p, p, p, i64, i64, i64, p, p, p]
         L.kvq_attn_score_error.argtypes = [p, i64, p, p, p, p, i64, i64, p, p]
         for name in ("kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
@@ -110,6 +114,15 @@ def kvq_quantize_fused(x, scales, codes, batch, N, D, stream=None):
            "kvq_quantize_fused")
 
 
+VARIANT_PRODUCTION, VARIANT_NAIVE, VARIANT_TILED, VARIANT_COARSENED, VARIANT_VECTORIZED = 0, 1, 2, 3, 4
+VARIANT_NAMES = {0: "production", 1: "naive", 2: "tiled", 3: "coarsened", 4: "vectorized"}
+
+
+def kvq_quantize_variant(variant, x, scales, codes, batch, N, D, stream=None):
+    _check(lib().kvq_quantize_variant(variant, _addr(x), _addr(scales), _addr(codes), batch, N, D, _stream(stream)),
+           "kvq_quantize_variant")
+
+
 def kvq_roundtrip_error(x, x_hat, codes, scales, batch, N, D, sumsq_out, maxabs_out, stream=None):
     _check(lib().kvq_roundtrip_error(_addr(x), _addr(x_hat), _addr(codes), _addr(scales), batch, N, D,
                                      _addr(sumsq_out), _addr(maxabs_out), _stream(stream)), "kvq_roundtrip_error")
@@ -118,6 +131,11 @@ def kvq_roundtrip_error(x, x_hat, codes, scales, batch, N, D, sumsq_out, maxabs_
 def kvq_attn_score_error(queries, Q, k, k_hat, codes, scales, N, D, mean_abs_out, stream=None):
     _check(lib().kvq_attn_score_error(_addr(queries), Q, _addr(k), _addr(k_hat), _addr(codes), _addr(scales),
                                       N, D, _addr(mean_abs_out), _stream(stream)), "kvq_attn_score_error")
+
+
+def kvq_probe_stream(mode, src_f32, dst_f32, src_i8, dst_i8, scales, batch, N, D, stream=None):
+    _check(lib().kvq_probe_stream(mode, _addr(src_f32), _addr(dst_f32), _addr(src_i8), _addr(dst_i8), _addr(scales),
+                                  batch, N, D, _stream(stream)), "kvq_probe_stream")
 
 
 def kvq_status_string(status):

@@ -1,6 +1,10 @@
 """Times every entry point of libkvq.so on each of the five configurations and prints a markdown table.
 
 Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
+        python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
+                                                                  [-1, 1], its four kernel designs next to
+                                                                  the production kernel, and its two error
+                                                                  figures computed on the GPU)
 Inputs are the seeded synthetic workloads, resident in HBM before timing; times are HIP-event
 minima and means over `iters` launches on torch's current stream.
 """
@@ -14,6 +18,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="1,2,3,4,5")
     ap.add_argument("--iters", type=int, default=20)
+    ap.add_argument("--paper-sweep", action="store_true")
     args = ap.parse_args()
     import torch
     from . import kvq, workloads as W
@@ -21,9 +26,13 @@ def main():
     stream = torch.cuda.current_stream()
 
     def timeit(f):
-        for _ in range(3):
-            f()
-        torch.cuda.synchronize()
+        # the first tens of milliseconds after an idle phase run at ramping clocks: warm up by time
+        import time
+        t_end = time.perf_counter() + 0.06
+        while time.perf_counter() < t_end:
+            for _ in range(5):
+                f()
+            torch.cuda.synchronize()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.iters + 1)]
         ev[0].record(stream)
         for i in range(args.iters):
@@ -32,6 +41,36 @@ def main():
         torch.cuda.synchronize()
         t = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.iters)]
         return float(np.mean(t)), float(np.min(t))
+
+    if args.paper_sweep:
+        names = [kvq.VARIANT_NAMES[v] for v in range(5)]
+        print("| shape (T x D) | " + " | ".join("%s ms (GB/s)" % n for n in names) +
+              " | dequantize ms (GB/s) | max-abs error | mean attention-score error (16 queries) |")
+        print("|---|" + "---|" * (len(names) + 3))
+        for label, (N, D) in W.PAPER_SHAPES.items():
+            E = N * D
+            x = torch.from_numpy(W.uniform_matrix(N, D, seed=0, stream=0)).cuda().reshape(-1)
+            q = torch.from_numpy(W.uniform_matrix(16, D, seed=0, stream=1)).cuda()
+            scales = torch.empty(D, dtype=torch.float32, device="cuda")
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            xh = torch.empty(E, dtype=torch.float32, device="cuda")
+            ss = torch.zeros(1, dtype=torch.float64, device="cuda")
+            mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+            mean = torch.zeros(1, dtype=torch.float64, device="cuda")
+            kvq.kvq_absmax_scales(x, scales, 1, N, D)
+            cells = []
+            for v in range(5):
+                m, _ = timeit(lambda: kvq.kvq_quantize_variant(v, x, scales, codes, 1, N, D))
+                cells.append("%.4f (%.0f)" % (m, 5.0 * E / m / 1e6))
+            m, _ = timeit(lambda: kvq.kvq_dequantize(codes, scales, xh, 1, N, D))
+            cells.append("%.4f (%.0f)" % (m, 5.0 * E / m / 1e6))
+            kvq.kvq_roundtrip_error(x, xh, None, None, 1, N, D, ss, mx)
+            kvq.kvq_attn_score_error(q, 16, x, xh, None, None, N, D, mean)
+            print("| %s (%d x %d) | %s | %.5f | %.4f |" % (label, N, D, " | ".join(cells), mx.item(), mean.item()))
+            sys.stdout.flush()
+            del x, codes, xh
+            torch.cuda.empty_cache()
+        return
 
     print("| cfg | shape | call | mean ms | min ms | algorithmic GB | GB/s (mean) | of 8 TB/s |")
     print("|---|---|---|---|---|---|---|---|")

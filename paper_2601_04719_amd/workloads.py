@@ -172,7 +172,31 @@ def queries(cfg, seed=0, n=None):
     return r.standard_normal(size=(q, c.D)).astype(np.float32)
 
 
-def uniform_matrix(N, D, seed=0, lo=-1.0, hi=1.0, stream=0):
-    """The paper's own fill (Evaluation, "Reconstruction Error": inputs in [-1, 1])."""
-    r = _rng(seed, 100, 0, stream)
-    return r.uniform(lo, hi, size=(N, D)).astype(np.float32)
+# The paper's own benchmark shapes (Tests, "Test configurations"): (tokens T, head dimension D).
+PAPER_SHAPES = {
+    "Small": (2048, 128), "Medium": (16384, 256), "Large": (65536, 256), "Very Large": (131072, 256),
+    "Realistic Small": (131072, 1024), "Realistic Medium": (131072, 2048),
+    "Realistic Large": (131072, 4096), "Realistic V. Large": (131072, 8192),
+}
+
+
+def uniform_matrix(N, D, seed=0, lo=-1.0, hi=1.0, stream=0, threads=None):
+    """The paper's own fill (Evaluation, "Reconstruction Error": inputs in [-1, 1]): float32 [N, D],
+    drawn in row chunks of about CHUNK_ELEMS elements so that large shapes can use several threads."""
+    out = np.empty((N, D), dtype=np.float32)
+    cr = max(1, CHUNK_ELEMS // D)
+    jobs = list(range(0, N, cr))
+
+    def run(r0):
+        r = _rng(seed, 100, D, stream, r0 // cr)
+        out[r0:r0 + cr] = r.uniform(lo, hi, size=(min(cr, N - r0), D))
+
+    if threads is None:
+        threads = min(16, os.cpu_count() or 1)
+    if threads <= 1 or len(jobs) <= 1:
+        for j in jobs:
+            run(j)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(run, jobs))
+    return out
