@@ -40,6 +40,8 @@ def lib():
             L.kvq_oracle_roundtrip_error.restype = None
             L.kvq_oracle_attn_score_error.argtypes = [_fp, _i64, _fp, _fp, _i64, _i64, _dp]
             L.kvq_oracle_attn_score_error.restype = None
+            L.kvq_oracle_scores_from_codes.argtypes = [_fp, _i64, _bp, _fp, _i64, _i64, _dp]
+            L.kvq_oracle_scores_from_codes.restype = None
             _lib = L
     return _lib
 
@@ -122,3 +124,17 @@ def attn_score_error(queries, k, k_hat):
     lib().kvq_oracle_attn_score_error(_ptr(queries, _fp), queries.shape[0], _ptr(k, _fp),
                                       _ptr(k_hat, _fp), k.shape[0], k.shape[1], ctypes.byref(r))
     return float(r.value)
+
+
+def scores_from_codes(queries, codes, scales):
+    """out[j, t] = q_j . k_hat_t with k_hat = float(code) * scale (fp32), dot product in fp64; [Q, N] float64."""
+    queries = _f32(queries)
+    scales = _f32(scales)
+    codes = np.ascontiguousarray(codes)
+    if codes.dtype != np.int8 or codes.ndim != 2 or queries.ndim != 2 or queries.shape[1] != codes.shape[1] \
+            or scales.size != codes.shape[1]:
+        raise ValueError("expected queries [Q, D] float32, codes [N, D] int8, scales [D] float32")
+    out = np.empty((queries.shape[0], codes.shape[0]), dtype=np.float64)
+    lib().kvq_oracle_scores_from_codes(_ptr(queries, _fp), queries.shape[0], _ptr(codes, _bp), _ptr(scales, _fp),
+                                       codes.shape[0], codes.shape[1], _ptr(out, _dp))
+    return out

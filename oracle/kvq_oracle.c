@@ -144,3 +144,26 @@ void kvq_oracle_attn_score_error(const float *queries, int64_t Q,
     }
     *mean_abs_out = total / ((double)Q * (double)N);
 }
+
+/* Attention scores straight from the quantized cache (Background, Eq. (attention): the scores are
+ * the dot products q.k, here with k replaced by its reconstruction of Eq. (dequant_op)):
+ * out[j,t] = sum_d q[j,d] * k_hat[t,d],  k_hat[t,d] = (float)codes[t,d] * scales[d] formed in fp32
+ * exactly as dequantization forms it, the dot product accumulated in fp64.  Raw dot products: no
+ * 1/sqrt(d) factor and no softmax. */
+void kvq_oracle_scores_from_codes(const float *queries, int64_t Q,
+                                  const int8_t *codes, const float *scales,
+                                  int64_t N, int64_t D, double *out)
+{
+    for (int64_t j = 0; j < Q; j++) {
+        const float *q = queries + (size_t)j * (size_t)D;
+        for (int64_t t = 0; t < N; t++) {
+            const int8_t *c = codes + (size_t)t * (size_t)D;
+            double a = 0.0;
+            for (int64_t d = 0; d < D; d++) {
+                float k_hat = (float)c[d] * scales[d];
+                a += (double)q[d] * (double)k_hat;
+            }
+            out[(size_t)j * (size_t)N + (size_t)t] = a;
+        }
+    }
+}

@@ -347,3 +347,40 @@ def test_batched_equals_per_slab():
         assert np.array_equal(sb, s[b])
         assert np.array_equal(oracle.quantize(x[b], sb), q[b])
         assert np.array_equal(oracle.dequantize(q[b], sb), xh[b])
+
+
+# --------------------------------------------------------------------------
+# scores straight from the quantized cache
+# --------------------------------------------------------------------------
+def test_scores_from_codes_hand_worked():
+    # codes [[1, -2], [127, 0], [-3, 4]], scales (0.5, 2) -> k_hat [[.5, -4], [63.5, 0], [-1.5, 8]]
+    codes = np.array([[1, -2], [127, 0], [-3, 4]], dtype=np.int8)
+    scales = np.array([0.5, 2.0], dtype=np.float32)
+    qs = np.array([[2.0, 1.0], [-1.0, 0.25]], dtype=np.float32)
+    out = oracle.scores_from_codes(qs, codes, scales)
+    # q0 = (2, 1):     1 - 4 = -3 ;  127 ;  -3 + 8 = 5
+    # q1 = (-1, .25): -.5 - 1 = -1.5 ; -63.5 ;  1.5 + 2 = 3.5
+    assert out.dtype == np.float64 and out.tolist() == [[-3.0, 127.0, 5.0], [-1.5, -63.5, 3.5]]
+
+
+def test_scores_from_codes_against_numpy_and_the_score_error():
+    x = workloads.generate(2, rows=(0, 1024))[0]
+    qs = workloads.queries(2)[:8]
+    s = oracle.compute_scales(x)
+    q = oracle.quantize(x, s)
+    xh = oracle.dequantize(q, s)
+    out = oracle.scores_from_codes(qs, q, s)
+    ref = qs.astype(np.float64) @ xh.astype(np.float64).T
+    assert np.allclose(out, ref, rtol=1e-13, atol=1e-12)
+    # consistency with the attention-score error: mean |q.k - (score from codes)|
+    exact = qs.astype(np.float64) @ x.astype(np.float64).T
+    assert np.abs(exact - out).mean() == pytest.approx(oracle.attn_score_error(qs, x, xh), rel=1e-10)
+    # a zero-scale channel contributes nothing, whatever its codes hold
+    s2 = s.copy()
+    s2[5] = 0.0
+    q2 = q.copy()
+    q2[:, 5] = 77
+    xh2 = xh.copy()
+    xh2[:, 5] = 0.0
+    assert np.allclose(oracle.scores_from_codes(qs, q2, s2), qs.astype(np.float64) @ xh2.astype(np.float64).T,
+                       rtol=1e-13, atol=1e-12)
