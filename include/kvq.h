@@ -145,6 +145,24 @@ kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
                                 double *mean_abs_out, kvq_stream_t stream);
 
 /*
+ * Attention scores straight from the quantized cache -- Background, Eq. (attention)
+ * (the raw dot products q.k, no 1/sqrt(d), no softmax) with k replaced by the
+ * reconstruction of Eq. (dequant_op):
+ *   scores_out[b,j,t] = sum_d queries[b,j,d] * ((float)codes[b,t,d] * scales[b,d])
+ * evaluated in fp32 with the scale folded into the query (q*s, then an FMA per
+ * code).  Against exact arithmetic the result is within
+ *   (16*ceil(D/1024) + 12) * 2^-24 * sum_d |queries * codes * scales|
+ * (generic kernel: (D + 4) * 2^-24 * the same sum).
+ *   queries [batch,Q,D] fp32, codes [batch,N,D] int8, scales [batch,D] fp32:
+ *   device, read only.  scores_out [batch,Q,N] fp32: device, written.
+ * Any Q >= 1; 8 queries are handled per pass over the codes.  D % 16 == 0 with
+ * 16-byte aligned inputs takes the fast kernel, anything else a generic one.
+ */
+kvq_status kvq_scores_from_codes(const float *queries, int64_t Q, const int8_t *codes,
+                                 const float *scales, int64_t batch, int64_t N, int64_t D,
+                                 float *scores_out, kvq_stream_t stream);
+
+/*
  * Measurement aid: no-math streaming kernels, to find what this GPU's memory
  * system sustains for the library's traffic patterns over a [batch,N,D] problem.
  *   mode 0: read the fp32 matrix src_f32                  (4 B/element; flat one-shot kernel)

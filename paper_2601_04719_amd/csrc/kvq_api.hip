@@ -190,6 +190,17 @@ kvq_status kvq_attn_score_error(const float* queries, int64_t Q, const float* k,
   return launch_attn_score_error(queries, Q, k, k_hat, codes, scales, N, D, mean_abs_out, stream);
 }
 
+kvq_status kvq_scores_from_codes(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
+                                 int64_t batch, int64_t N, int64_t D, float* scores_out, kvq_stream_t stream) {
+  if (!queries || !codes || !scales || !scores_out) return KVQ_ERR_NULL;
+  if (Q < 1) return KVQ_ERR_SHAPE;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (Q > INT32_MAX || Q > (INT64_MAX / 8) / D || batch > (INT64_MAX / 8) / (Q * D) || Q > (INT64_MAX / 8) / N ||
+      batch > (INT64_MAX / 8) / (Q * N))
+    return KVQ_ERR_OVERFLOW;
+  return launch_scores_from_codes(queries, Q, codes, scales, batch, N, D, scores_out, stream);
+}
+
 const char* kvq_status_string(kvq_status status) {
   switch (status) {
     case KVQ_OK: return "KVQ_OK";

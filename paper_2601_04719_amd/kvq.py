@@ -21,7 +21,7 @@ OPT_ABSMAX_BLOCKS_PER_CU = 11
 
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
-    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_probe_stream", "kvq_status_string",
+    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
 )
 
@@ -52,6 +52,8 @@ def lib():
         L.kvq_quantize_fused.argtypes = [p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.restype = i32
+        L.kvq_scores_from_codes.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
+        L.kvq_scores_from_codes.restype = i32
         L.kvq_probe_stream.argtypes = [i32, p, p, p, p, p, i64, i64, i64, p]
         L.kvq_probe_stream.restype = i32
         L.kvq_roundtrip_error.argtypes = [p, p, p, p, i64, i64, i64, p, p, p]
@@ -131,6 +133,11 @@ def kvq_roundtrip_error(x, x_hat, codes, scales, batch, N, D, sumsq_out, maxabs_
 def kvq_attn_score_error(queries, Q, k, k_hat, codes, scales, N, D, mean_abs_out, stream=None):
     _check(lib().kvq_attn_score_error(_addr(queries), Q, _addr(k), _addr(k_hat), _addr(codes), _addr(scales),
                                       N, D, _addr(mean_abs_out), _stream(stream)), "kvq_attn_score_error")
+
+
+def kvq_scores_from_codes(queries, Q, codes, scales, batch, N, D, scores_out, stream=None):
+    _check(lib().kvq_scores_from_codes(_addr(queries), Q, _addr(codes), _addr(scales), batch, N, D,
+                                       _addr(scores_out), _stream(stream)), "kvq_scores_from_codes")
 
 
 def kvq_probe_stream(mode, src_f32, dst_f32, src_i8, dst_i8, scales, batch, N, D, stream=None):

@@ -1,6 +1,7 @@
 """Times every entry point of libkvq.so on each of the five configurations and prints a markdown table.
 
 Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
+        python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
                                                                   the production kernel, and its two error
@@ -19,6 +20,7 @@ def main():
     ap.add_argument("--configs", default="1,2,3,4,5")
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--paper-sweep", action="store_true")
+    ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
     from . import kvq, workloads as W
@@ -41,6 +43,25 @@ def main():
         torch.cuda.synchronize()
         t = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.iters)]
         return float(np.mean(t)), float(np.min(t))
+
+    if args.scores:
+        print("| batch x N x D | Q | mean ms | bytes moved (GB) | GB/s | of 8 TB/s | fp32 TFLOP/s |")
+        print("|---|---|---|---|---|---|---|")
+        for (B, N, D) in [(256, 4096, 128), (2048, 4096, 128), (32, 131072, 128), (1, 1048576, 128), (1, 131072, 8192)]:
+            E = B * N * D
+            codes = torch.randint(-127, 128, (E,), dtype=torch.int8, device="cuda")
+            scales = torch.rand(B * D, device="cuda") + 0.1
+            for Q in (1, 2, 4, 8):
+                q = torch.randn(B * Q * D, device="cuda")
+                out = torch.empty(B * Q * N, device="cuda")
+                m, _ = timeit(lambda: kvq.kvq_scores_from_codes(q, Q, codes, scales, B, N, D, out))
+                nbytes = E + 4.0 * B * Q * N + 4.0 * B * Q * D + 4.0 * B * D
+                print("| %d x %d x %d | %d | %.4f | %.4f | %.0f | %.3f | %.1f |" % (
+                    B, N, D, Q, m, nbytes / 1e9, nbytes / m / 1e6, nbytes / m / 1e6 / 8000.0, 2.0 * Q * E / m / 1e9))
+                sys.stdout.flush()
+            del codes
+            torch.cuda.empty_cache()
+        return
 
     if args.paper_sweep:
         names = [kvq.VARIANT_NAMES[v] for v in range(5)]

@@ -308,6 +308,43 @@ def test_paper_error_figures_on_the_gpu_path():
     assert abs(a - 0.095) < 0.0025                                # Evaluation, "Attention Score Error"
 
 
+# ------------------------------------------------------------------ scores straight from the quantized cache
+def scores_bound(D, fast):
+    """Worst-case |gpu - exact| per unit of sum_d |q k_hat|: fp32 rounding of q*s (vs the oracle's
+    rounding of code*s), one fp32 FMA per code in a lane's chain (16 per 1024-channel chunk, or D in
+    the generic kernel), up to 6 cross-lane adds, and the final value kept in fp32."""
+    n = 16 * -(-D // 1024) + 12 if fast else D + 4
+    return n * 2.0 ** -24
+
+
+@pytest.mark.parametrize("shape,Q", [((1, 1024, 64), 16), ((1, 4096, 128), 1), ((6, 1000, 128), 8), ((3, 257, 128), 5),
+                                     ((1, 300, 80), 3), ((2, 100, 1024), 2), ((1, 50, 4096), 9), ((1, 33, 100), 4),
+                                     ((2, 1, 16), 1), ((1, 70, 20), 2)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else "Q%d" % v)
+def test_scores_from_codes(shape, Q):
+    batch, N, D = shape
+    rng = np.random.default_rng(N + D + Q)
+    x = make_matrix(rng, batch, N, D)
+    qs = rng.standard_normal((batch, Q, D)).astype(np.float32)
+    s_ref = oracle.compute_scales(x)
+    q_ref = oracle.quantize(x, s_ref)
+    g = Gpu(x)
+    g.set_scales(s_ref)
+    g.codes.copy_(torch.from_numpy(q_ref.reshape(-1)))
+    qd = torch.from_numpy(qs).cuda()
+    out = torch.full((batch * Q * N + 8,), 555.0, dtype=torch.float32, device="cuda")
+    kvq.kvq_scores_from_codes(qd, Q, g.codes, g.scales, batch, N, D, out)
+    got = out[:batch * Q * N].cpu().numpy().reshape(batch, Q, N).astype(np.float64)
+    assert bool((out[batch * Q * N:] == 555.0).all())
+    fast = D % 16 == 0
+    for b in range(batch):
+        ref = oracle.scores_from_codes(qs[b], q_ref[b], s_ref[b])
+        xh = oracle.dequantize(q_ref[b], s_ref[b]).astype(np.float64)
+        mag = np.abs(qs[b].astype(np.float64)) @ np.abs(xh).T
+        err = np.abs(got[b] - ref)
+        assert (err <= scores_bound(D, fast) * mag + 1e-300).all(), (b, float((err / (mag + 1e-300)).max()))
+
+
 FUSED_SHAPES = [(7, 512, 128), (3, 1000, 64), (2, 16, 4096), (5, 17, 20), (1, 16384, 4), (1, 16385, 4),
                 (4, 2048, 32), (9, 1, 8), (2, 513, 128), (1, 65, 1024), (300, 64, 64)]
 
