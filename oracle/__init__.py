@@ -138,3 +138,38 @@ def scores_from_codes(queries, codes, scales):
     lib().kvq_oracle_scores_from_codes(_ptr(queries, _fp), queries.shape[0], _ptr(codes, _bp), _ptr(scales, _fp),
                                        codes.shape[0], codes.shape[1], _ptr(out, _dp))
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# 16-bit matrices ("Memory Bottleneck in LLM Inference": caches are kept in FP16-class formats).
+# A 16-bit value widens to fp32 exactly, so scales and codes of a 16-bit matrix are those of the
+# widened matrix; dequantization rounds the fp32 product once more, to nearest even.
+# ---------------------------------------------------------------------------------------------
+def widen16(bits, fmt):
+    """uint16 bit patterns of fp16 ('f16') or bfloat16 ('bf16') values -> float32 (exact)."""
+    bits = np.ascontiguousarray(bits)
+    if bits.dtype != np.uint16:
+        raise TypeError("expected uint16 bit patterns")
+    if fmt == "f16":
+        return bits.view(np.float16).astype(np.float32)
+    if fmt == "bf16":
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    raise ValueError(fmt)
+
+
+def narrow16(x, fmt):
+    """float32 -> nearest fp16 / bfloat16 (ties to even), as uint16 bit patterns.  Finite inputs."""
+    x = _f32(x)
+    if fmt == "f16":
+        with np.errstate(over="ignore"):
+            return x.astype(np.float16).view(np.uint16)
+    if fmt == "bf16":
+        u = x.view(np.uint32).astype(np.uint64)
+        lsb = (u >> np.uint64(16)) & np.uint64(1)            # parity of the kept part decides a tie
+        return ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+    raise ValueError(fmt)
+
+
+def dequantize_as(codes, scales, fmt):
+    """x_hat = round_to_16bit(float32(code) * scale): Eq. (dequant_op) in fp32, then one rounding."""
+    return narrow16(dequantize(codes, scales), fmt)

@@ -384,3 +384,54 @@ def test_scores_from_codes_against_numpy_and_the_score_error():
     xh2[:, 5] = 0.0
     assert np.allclose(oracle.scores_from_codes(qs, q2, s2), qs.astype(np.float64) @ xh2.astype(np.float64).T,
                        rtol=1e-13, atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# 16-bit formats
+# --------------------------------------------------------------------------
+def _nearest_16bit(fr: Fraction, mant_bits: int, emin: int) -> Fraction:
+    """Nearest value with `mant_bits` explicit mantissa bits (ties to even, gradual underflow)."""
+    if fr == 0:
+        return Fraction(0)
+    sign = -1 if fr < 0 else 1
+    a = abs(fr)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    e = max(e, emin)
+    ulp = Fraction(2) ** (e - mant_bits)
+    return sign * round_half_even(a / ulp) * ulp
+
+
+@pytest.mark.parametrize("fmt,mant,emin", [("f16", 10, -14), ("bf16", 7, -126)])
+def test_narrowing_to_16_bit_is_round_to_nearest_even(fmt, mant, emin):
+    rng = np.random.default_rng(23)
+    vals = (rng.standard_normal(300) * np.exp(rng.uniform(-8, 8, 300))).astype(np.float32)
+    # exact ties and their neighbours: k + 1/2 units in the last place of the 16-bit format
+    base = np.float32(1.0)
+    ulp = np.float32(2.0 ** -mant)
+    ties = np.array([base + ulp * (k + 0.5) for k in range(8)], dtype=np.float32)
+    vals = np.concatenate([vals, ties, np.nextafter(ties, np.float32(9)), np.nextafter(ties, np.float32(0)),
+                           -ties, np.array([0.0, 2.0 ** -20, 3e-6, 60000.0], dtype=np.float32)])
+    bits = oracle.narrow16(vals, fmt)
+    back = oracle.widen16(bits, fmt)
+    for v, b in zip(vals, back):
+        assert Fraction(float(b)) == _nearest_16bit(Fraction(float(v)), mant, emin), (fmt, float(v))
+    # widening is exact and narrowing a representable value is the identity
+    assert np.array_equal(oracle.narrow16(back, fmt), bits)
+
+
+def test_dequantize_as_16_bit_rounds_the_fp32_product_once():
+    x = workloads.generate(1)[0]
+    for fmt in ("f16", "bf16"):
+        x16 = oracle.narrow16(x, fmt)
+        xw = oracle.widen16(x16, fmt)
+        s = oracle.compute_scales(xw)
+        q = oracle.quantize(xw, s)
+        xh16 = oracle.dequantize_as(q, s, fmt)
+        xh32 = oracle.dequantize(q, s)
+        assert np.array_equal(xh16, oracle.narrow16(xh32, fmt))
+        # the round trip through the 16-bit format stays within the bound plus half a 16-bit ulp
+        err = np.abs(xw.astype(np.float64) - oracle.widen16(xh16, fmt).astype(np.float64))
+        ulp16 = np.abs(xh32.astype(np.float64)) * 2.0 ** (-10 if fmt == "f16" else -7)
+        assert (err <= s.astype(np.float64)[None, :] / 2 * (1 + 2.0 ** -15) + ulp16 / 2 + 1e-30).all()
