@@ -81,6 +81,25 @@ kvq_status kvq_dequantize(const int8_t *codes, const float *scales, float *x_hat
                           int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
 
 /*
+ * The three calls above for matrices kept in fp16 or bf16 (the formats real caches
+ * use; "Memory Bottleneck in LLM Inference").  x / x_hat point to 16-bit elements
+ * in the same [batch,N,D] layout.  A 16-bit value widens to fp32 exactly, so scales
+ * and codes are those of the widened matrix; dequantization forms (float)code *
+ * scale in fp32 and rounds it to nearest even into the 16-bit format.  Scales stay
+ * fp32.  dtype KVQ_DTYPE_F32 forwards to the fp32 calls; an unknown dtype or an
+ * odd 16-bit pointer gives KVQ_ERR_ARG.
+ */
+#define KVQ_DTYPE_F32 0
+#define KVQ_DTYPE_F16 1
+#define KVQ_DTYPE_BF16 2
+kvq_status kvq_absmax_scales_t(int dtype, const void *x, float *scales,
+                               int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+kvq_status kvq_quantize_t(int dtype, const void *x, const float *scales, int8_t *codes,
+                          int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+kvq_status kvq_dequantize_t(int dtype, const int8_t *codes, const float *scales, void *x_hat,
+                            int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
  * Scale computation and quantization in one call (same results as
  * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
  * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in

@@ -146,6 +146,36 @@ kvq_status kvq_dequantize(const int8_t* codes, const float* scales, float* x_hat
   return launch_dequantize(codes, scales, x_hat, batch, N, D, stream);
 }
 
+kvq_status kvq_absmax_scales_t(int dtype, const void* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                               kvq_stream_t stream) {
+  if (!x || !scales) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (dtype == KVQ_DTYPE_F32) return launch_absmax_scales(static_cast<const float*>(x), scales, batch, N, D, stream);
+  if (dtype != KVQ_DTYPE_F16 && dtype != KVQ_DTYPE_BF16) return KVQ_ERR_ARG;
+  if (!aligned(x, 2)) return KVQ_ERR_ARG;
+  return launch_absmax_scales_16(dtype, x, scales, batch, N, D, stream);
+}
+
+kvq_status kvq_quantize_t(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                          int64_t D, kvq_stream_t stream) {
+  if (!x || !scales || !codes) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (dtype == KVQ_DTYPE_F32) return launch_quantize(static_cast<const float*>(x), scales, codes, batch, N, D, stream);
+  if (dtype != KVQ_DTYPE_F16 && dtype != KVQ_DTYPE_BF16) return KVQ_ERR_ARG;
+  if (!aligned(x, 2)) return KVQ_ERR_ARG;
+  return launch_quantize_16(dtype, x, scales, codes, batch, N, D, stream);
+}
+
+kvq_status kvq_dequantize_t(int dtype, const int8_t* codes, const float* scales, void* x_hat, int64_t batch,
+                            int64_t N, int64_t D, kvq_stream_t stream) {
+  if (!codes || !scales || !x_hat) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (dtype == KVQ_DTYPE_F32) return launch_dequantize(codes, scales, static_cast<float*>(x_hat), batch, N, D, stream);
+  if (dtype != KVQ_DTYPE_F16 && dtype != KVQ_DTYPE_BF16) return KVQ_ERR_ARG;
+  if (!aligned(x_hat, 2)) return KVQ_ERR_ARG;
+  return launch_dequantize_16(dtype, codes, scales, x_hat, batch, N, D, stream);
+}
+
 kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N,
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;

@@ -102,6 +102,12 @@ kvq_status launch_probe_codec(int mode, const float* src_f32, float* dst_f32, co
                               hipStream_t stream);
 kvq_status launch_scores_from_codes(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
                                     int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream);
+kvq_status launch_absmax_scales_16(int dtype, const void* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                   hipStream_t stream);
+kvq_status launch_quantize_16(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,
+                              int64_t N, int64_t D, hipStream_t stream);
+kvq_status launch_dequantize_16(int dtype, const int8_t* codes, const float* scales, void* x_hat, int64_t batch,
+                                int64_t N, int64_t D, hipStream_t stream);
 kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int64_t count, double* sumsq_out,
                                         float* maxabs_out, hipStream_t stream);
 kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, const float* scales,

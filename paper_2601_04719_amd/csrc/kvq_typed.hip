@@ -1,0 +1,379 @@
+// The same scale computation, quantization and dequantization for fp16 and bf16 matrices
+// (paper: "Memory Bottleneck in LLM Inference" notes that real caches are kept in 16-bit formats;
+//  the arithmetic is that of Eq. (scale_compute), Eq. (quant_op), Eq. (dequant_op)).
+//
+// A 16-bit value converts to fp32 exactly, so scales and codes are what the fp32 path would give
+// for the widened matrix; dequantization forms (float)code * scale in fp32 and rounds it once more,
+// to nearest even, into the 16-bit format.  Traffic is 2 B in + 1 B out per element (or the
+// reverse).  A lane owns 8 adjacent channels: one 16-byte access on the 16-bit side, one 8-byte
+// access on the code side, both contiguous across a wavefront.
+#include <type_traits>
+
+#include "kvq_internal.h"
+
+namespace kvq {
+
+struct f16_tag {};
+struct bf16_tag {};
+
+typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+
+// ---- element conversions -----------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float widen(uint16_t bits);
+template <>
+__device__ __forceinline__ float widen<f16_tag>(uint16_t bits) {
+  _Float16 h;
+  __builtin_memcpy(&h, &bits, 2);
+  return (float)h;
+}
+template <>
+__device__ __forceinline__ float widen<bf16_tag>(uint16_t bits) {
+  return __uint_as_float((uint32_t)bits << 16);
+}
+
+// round to nearest even (finite inputs)
+template <typename T>
+__device__ __forceinline__ uint16_t narrow(float v);
+template <>
+__device__ __forceinline__ uint16_t narrow<f16_tag>(float v) {
+  const _Float16 h = (_Float16)v;
+  uint16_t bits;
+  __builtin_memcpy(&bits, &h, 2);
+  return bits;
+}
+template <>
+__device__ __forceinline__ uint16_t narrow<bf16_tag>(float v) {
+  const uint32_t u = __float_as_uint(v);
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ void widen8(const u16x8& raw, float (&out)[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; i++) out[i] = widen<T>(raw[i]);
+}
+
+constexpr float kMagic16 = 12582912.0f;  // 1.5 * 2^23, see the fp32 quantize kernel
+
+// Plain IEEE divide: a reciprocal-multiply shortcut with an exact fallback near ties was measured on
+// this kernel too (3 bytes of traffic per element) and was slower (4.1-4.9 TB/s against 5.2).
+__device__ __forceinline__ uint32_t code_byte(float x, float div) {
+  float y = x / div;
+  y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
+  return __float_as_uint(y + kMagic16) & 0xffu;
+}
+
+// ---- absmax --------------------------------------------------------------------------------
+// V = 8 (vector) or 1 (scalar); J column groups per lane, TX groups apart (see the fp32 kernel)
+template <typename T, int V, int J, int U>
+__global__ __launch_bounds__(kBlock) void absmax16_kernel(const uint16_t* __restrict__ x,
+                                                          uint32_t* __restrict__ max_bits, int64_t N, int64_t D,
+                                                          int tx_log2, uint32_t ctiles, uint32_t rchunks,
+                                                          int64_t rows_per_chunk, int64_t groups) {
+  __shared__ float red[J == 1 ? kBlock * V : 1];
+  const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
+  const int TX = 1 << tx_log2;
+  const int tx = threadIdx.x & (TX - 1);
+  const int64_t group0 = (it.group - tx) * J + tx;
+  float m[J][V];
+  bool act[J];
+#pragma unroll
+  for (int j = 0; j < J; j++) {
+    act[j] = group0 + (int64_t)j * TX < groups;
+#pragma unroll
+    for (int i = 0; i < V; i++) m[j][i] = 0.0f;
+  }
+  if (act[0]) {
+    const int64_t step = (int64_t)it.TY * D;
+    int64_t row = it.row0 + it.ty;
+    const uint16_t* p = x + (it.slab * N + row) * D + group0 * V;
+    if constexpr (V == 8) {
+      auto do_rows = [&](auto tag) {
+        constexpr int R = decltype(tag)::value;
+        u16x8 v[R][J];
+#pragma unroll
+        for (int u = 0; u < R; u++)
+#pragma unroll
+          for (int j = 0; j < J; j++) {
+            v[u][j] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (J == 1 || act[j])
+              v[u][j] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(p + u * step) + (int64_t)j * TX);
+          }
+#pragma unroll
+        for (int u = 0; u < R; u++)
+#pragma unroll
+          for (int j = 0; j < J; j++) {
+            float f[8];
+            widen8<T>(v[u][j], f);
+#pragma unroll
+            for (int i = 0; i < 8; i++) m[j][i] = fmaxf(m[j][i], fabsf(f[i]));
+          }
+      };
+      for (; row + (int64_t)(U - 1) * it.TY < it.row1; row += (int64_t)U * it.TY, p += U * step)
+        do_rows(std::integral_constant<int, U>{});
+      for (; row < it.row1; row += it.TY, p += step) do_rows(std::integral_constant<int, 1>{});
+    } else {
+      for (; row < it.row1; row += it.TY, p += step) m[0][0] = fmaxf(m[0][0], fabsf(widen<T>(*p)));
+    }
+  }
+  if constexpr (J == 1) {
+    if (it.TY > 1) {
+#pragma unroll
+      for (int i = 0; i < V; i++) red[i * kBlock + threadIdx.x] = m[0][i];
+      __syncthreads();
+      if (it.ty == 0) {
+        for (int y = 1; y < it.TY; y++) {
+#pragma unroll
+          for (int i = 0; i < V; i++) m[0][i] = fmaxf(m[0][i], red[i * kBlock + y * TX + threadIdx.x]);
+        }
+      }
+    }
+  }
+  if (it.ty == 0) {
+#pragma unroll
+    for (int j = 0; j < J; j++) {
+      if (!act[j]) continue;
+      uint32_t* out = max_bits + it.slab * D + (group0 + (int64_t)j * TX) * V;
+#pragma unroll
+      for (int i = 0; i < V; i++) {
+        const uint32_t bits = __float_as_uint(m[j][i]);
+        if (bits != 0u) atomicMax(out + i, bits);
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void fill_zero16(uint32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+__global__ __launch_bounds__(kBlock) void finalize16(float* scales, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) scales[i] = scales[i] / 127.0f;
+}
+
+// ---- quantize --------------------------------------------------------------------------------
+template <typename T, int V, int U>
+__global__ __launch_bounds__(kMaxBlock) void quantize16_kernel(const uint16_t* __restrict__ x,
+                                                               const float* __restrict__ scales,
+                                                               int8_t* __restrict__ codes, int64_t N, int64_t D,
+                                                               int tx_log2, uint32_t ctiles, uint32_t rchunks,
+                                                               int64_t rows_per_chunk, int64_t groups) {
+  const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
+  if (it.group >= groups) return;
+  const int64_t col = it.group * V;
+  float div[V];
+  if constexpr (V == 8) {
+#pragma unroll
+    for (int w = 0; w < 2; w++) {
+      const f32x4 sv = *(reinterpret_cast<const f32x4*>(scales + it.slab * D + col) + w);
+#pragma unroll
+      for (int i = 0; i < 4; i++) div[4 * w + i] = sv[i] == 0.0f ? __builtin_inff() : sv[i];
+    }
+  } else {
+    const float s = scales[it.slab * D + col];
+    div[0] = s == 0.0f ? __builtin_inff() : s;
+  }
+  const int64_t step = (int64_t)it.TY * D;
+  int64_t row = it.row0 + it.ty;
+  const uint16_t* px = x + (it.slab * N + row) * D + col;
+  int8_t* pc = codes + (it.slab * N + row) * D + col;
+  if constexpr (V == 8) {
+    auto do_rows = [&](auto tag) {
+      constexpr int R = decltype(tag)::value;
+      u16x8 v[R];
+#pragma unroll
+      for (int u = 0; u < R; u++) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(px + u * step));
+#pragma unroll
+      for (int u = 0; u < R; u++) {
+        float f[8];
+        widen8<T>(v[u], f);
+        u32x2 c;
+#pragma unroll
+        for (int w = 0; w < 2; w++) {
+          uint32_t word = 0;
+#pragma unroll
+          for (int b = 0; b < 4; b++) word |= code_byte(f[4 * w + b], div[4 * w + b]) << (8 * b);
+          c[w] = word;
+        }
+        __builtin_nontemporal_store(c, reinterpret_cast<u32x2*>(pc + u * step));
+      }
+    };
+    for (; row + (int64_t)(U - 1) * it.TY < it.row1; row += (int64_t)U * it.TY, px += U * step, pc += U * step)
+      do_rows(std::integral_constant<int, U>{});
+    for (; row < it.row1; row += it.TY, px += step, pc += step) do_rows(std::integral_constant<int, 1>{});
+  } else {
+    for (; row < it.row1; row += it.TY, px += step, pc += step) *pc = (int8_t)code_byte(widen<T>(*px), div[0]);
+  }
+}
+
+// ---- dequantize --------------------------------------------------------------------------------
+template <typename T, int V, int U>
+__global__ __launch_bounds__(kMaxBlock) void dequantize16_kernel(const int8_t* __restrict__ codes,
+                                                                 const float* __restrict__ scales,
+                                                                 uint16_t* __restrict__ x_hat, int64_t N, int64_t D,
+                                                                 int tx_log2, uint32_t ctiles, uint32_t rchunks,
+                                                                 int64_t rows_per_chunk, int64_t groups) {
+  const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
+  if (it.group >= groups) return;
+  const int64_t col = it.group * V;
+  float s[V];
+  if constexpr (V == 8) {
+#pragma unroll
+    for (int w = 0; w < 2; w++) {
+      const f32x4 sv = *(reinterpret_cast<const f32x4*>(scales + it.slab * D + col) + w);
+#pragma unroll
+      for (int i = 0; i < 4; i++) s[4 * w + i] = sv[i];
+    }
+  } else {
+    s[0] = scales[it.slab * D + col];
+  }
+  const int64_t step = (int64_t)it.TY * D;
+  int64_t row = it.row0 + it.ty;
+  const int8_t* pc = codes + (it.slab * N + row) * D + col;
+  uint16_t* px = x_hat + (it.slab * N + row) * D + col;
+  if constexpr (V == 8) {
+    auto do_rows = [&](auto tag) {
+      constexpr int R = decltype(tag)::value;
+      u32x2 c[R];
+#pragma unroll
+      for (int u = 0; u < R; u++) c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(pc + u * step));
+#pragma unroll
+      for (int u = 0; u < R; u++) {
+        u16x8 o;
+#pragma unroll
+        for (int w = 0; w < 2; w++)
+#pragma unroll
+          for (int b = 0; b < 4; b++) {
+            const int q = (int)(c[u][w] << (24 - 8 * b)) >> 24;
+            o[4 * w + b] = narrow<T>((float)q * s[4 * w + b]);
+          }
+        __builtin_nontemporal_store(o, reinterpret_cast<u16x8*>(px + u * step));
+      }
+    };
+    for (; row + (int64_t)(U - 1) * it.TY < it.row1; row += (int64_t)U * it.TY, px += U * step, pc += U * step)
+      do_rows(std::integral_constant<int, U>{});
+    for (; row < it.row1; row += it.TY, px += step, pc += step) do_rows(std::integral_constant<int, 1>{});
+  } else {
+    for (; row < it.row1; row += it.TY, px += step, pc += step) *px = narrow<T>((float)(*pc) * s[0]);
+  }
+}
+
+// ---- launchers ---------------------------------------------------------------------------------
+static Tiling oneshot_tiling(int64_t batch, int64_t N, int64_t D, int V, int U, int block, int cus,
+                             int passes = 1) {
+  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)cus * 8, block, passes);
+  while (t.items > ((int64_t)1 << 30) && passes < (1 << 20)) {
+    passes *= 2;
+    t = make_tiling(batch, N, D, V, U, (int64_t)cus * 8, block, passes);
+  }
+  return t;
+}
+
+template <typename T>
+static kvq_status absmax16(const uint16_t* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                           hipStream_t stream) {
+  const DeviceInfo dev = current_device();
+  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  const int V = (D % 8 == 0 && aligned(x, 16)) ? 8 : 1;
+  int J = 1;
+  if (V == 8) {
+    const int64_t groups = D / 8;
+    while (J < 4 && (int64_t)kBlock * J < groups) J *= 2;
+  }
+  constexpr int U1 = 8, UJ = 2;
+  const int U = J == 1 ? U1 : UJ;
+  // narrow rows: four workgroups per compute unit hide the conversion work behind each other's loads;
+  // wide rows: one, because every extra row chunk costs a full row of atomics at the end
+  const int bpc = J == 1 ? 4 : 1;
+  Tiling t = make_tiling(batch, N, D, V * J, U, (int64_t)dev.cus * bpc, kBlock, 0);
+  if (J > 1) {
+    t.tx_log2 = 8;
+    t.groups = D / V;
+    t.ctiles = (uint32_t)((t.groups + (int64_t)kBlock * J - 1) / ((int64_t)kBlock * J));
+    t.items = batch * (int64_t)t.rchunks * t.ctiles;
+  }
+  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  const int64_t n_scales = batch * D;
+  const int64_t small = (n_scales + kBlock - 1) / kBlock;
+  if (small > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  uint32_t* bits = reinterpret_cast<uint32_t*>(scales);
+  hipLaunchKernelGGL(fill_zero16, dim3((uint32_t)small), dim3(kBlock), 0, stream, bits, n_scales);
+  KVQ_HIP(hipGetLastError());
+  const dim3 grid((uint32_t)t.items), block(kBlock);
+#define KVQ_AM16(V_, J_, U_)                                                                                   \
+  hipLaunchKernelGGL((absmax16_kernel<T, V_, J_, U_>), grid, block, 0, stream, x, bits, N, D, t.tx_log2, t.ctiles, \
+                     t.rchunks, t.rows_per_chunk, t.groups)
+  if (V == 1) KVQ_AM16(1, 1, U1);
+  else if (J == 1) KVQ_AM16(8, 1, U1);
+  else if (J == 2) KVQ_AM16(8, 2, UJ);
+  else KVQ_AM16(8, 4, UJ);
+#undef KVQ_AM16
+  KVQ_HIP(hipGetLastError());
+  hipLaunchKernelGGL(finalize16, dim3((uint32_t)small), dim3(kBlock), 0, stream, scales, n_scales);
+  KVQ_HIP(hipGetLastError());
+  return KVQ_OK;
+}
+
+template <typename T>
+static kvq_status quantize16(const uint16_t* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                             int64_t D, hipStream_t stream) {
+  const DeviceInfo dev = current_device();
+  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  const bool vec = D % 8 == 0 && aligned(x, 16) && aligned(codes, 8) && aligned(scales, 16);
+  constexpr int U = 4;
+  const Tiling t = oneshot_tiling(batch, N, D, vec ? 8 : 1, vec ? U : 1, 256, dev.cus, 2);  // 2 passes: +4 %
+  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  const dim3 grid((uint32_t)t.items), block(t.block);
+  if (vec)
+    hipLaunchKernelGGL((quantize16_kernel<T, 8, U>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  else
+    hipLaunchKernelGGL((quantize16_kernel<T, 1, 1>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  KVQ_HIP(hipGetLastError());
+  return KVQ_OK;
+}
+
+template <typename T>
+static kvq_status dequantize16(const int8_t* codes, const float* scales, uint16_t* x_hat, int64_t batch, int64_t N,
+                               int64_t D, hipStream_t stream) {
+  const DeviceInfo dev = current_device();
+  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  const bool vec = D % 8 == 0 && aligned(x_hat, 16) && aligned(codes, 8) && aligned(scales, 16);
+  constexpr int U = 2;
+  const Tiling t = oneshot_tiling(batch, N, D, vec ? 8 : 1, vec ? U : 1, 256, dev.cus);
+  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  const dim3 grid((uint32_t)t.items), block(t.block);
+  if (vec)
+    hipLaunchKernelGGL((dequantize16_kernel<T, 8, U>), grid, block, 0, stream, codes, scales, x_hat, N, D,
+                       t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  else
+    hipLaunchKernelGGL((dequantize16_kernel<T, 1, 1>), grid, block, 0, stream, codes, scales, x_hat, N, D,
+                       t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+  KVQ_HIP(hipGetLastError());
+  return KVQ_OK;
+}
+
+kvq_status launch_absmax_scales_16(int dtype, const void* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                   hipStream_t stream) {
+  const uint16_t* p = static_cast<const uint16_t*>(x);
+  return dtype == KVQ_DTYPE_F16 ? absmax16<f16_tag>(p, scales, batch, N, D, stream)
+                                : absmax16<bf16_tag>(p, scales, batch, N, D, stream);
+}
+kvq_status launch_quantize_16(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,
+                              int64_t N, int64_t D, hipStream_t stream) {
+  const uint16_t* p = static_cast<const uint16_t*>(x);
+  return dtype == KVQ_DTYPE_F16 ? quantize16<f16_tag>(p, scales, codes, batch, N, D, stream)
+                                : quantize16<bf16_tag>(p, scales, codes, batch, N, D, stream);
+}
+kvq_status launch_dequantize_16(int dtype, const int8_t* codes, const float* scales, void* x_hat, int64_t batch,
+                                int64_t N, int64_t D, hipStream_t stream) {
+  uint16_t* p = static_cast<uint16_t*>(x_hat);
+  return dtype == KVQ_DTYPE_F16 ? dequantize16<f16_tag>(codes, scales, p, batch, N, D, stream)
+                                : dequantize16<bf16_tag>(codes, scales, p, batch, N, D, stream);
+}
+
+}  // namespace kvq

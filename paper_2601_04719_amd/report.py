@@ -1,6 +1,7 @@
 """Times every entry point of libkvq.so on each of the five configurations and prints a markdown table.
 
 Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
+        python -m paper_2601_04719_amd.report --sixteen          (fp16 / bf16 matrices)
         python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
@@ -20,6 +21,7 @@ def main():
     ap.add_argument("--configs", default="1,2,3,4,5")
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--paper-sweep", action="store_true")
+    ap.add_argument("--sixteen", action="store_true", help="fp16 / bf16 matrices: absmax, quantize, dequantize")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
@@ -43,6 +45,26 @@ def main():
         torch.cuda.synchronize()
         t = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.iters)]
         return float(np.mean(t)), float(np.min(t))
+
+    if args.sixteen:
+        print("| format | batch x N x D | absmax ms (GB/s, of 8 TB/s) | quantize ms (GB/s, of 8 TB/s) | dequantize ms (GB/s, of 8 TB/s) |")
+        print("|---|---|---|---|---|")
+        for (B, N, D) in [(1, 131072, 8192), (1, 16384, 8192), (256, 4096, 128), (2048, 4096, 128)]:
+            E = B * N * D
+            for name, dt, tdt in (("fp16", kvq.DTYPE_F16, torch.float16), ("bf16", kvq.DTYPE_BF16, torch.bfloat16)):
+                x = torch.randn(E, device="cuda").to(tdt)
+                scales = torch.empty(B * D, device="cuda")
+                codes = torch.empty(E, dtype=torch.int8, device="cuda")
+                xh = torch.empty(E, dtype=tdt, device="cuda")
+                ta, _ = timeit(lambda: kvq.kvq_absmax_scales_t(dt, x, scales, B, N, D))
+                tq, _ = timeit(lambda: kvq.kvq_quantize_t(dt, x, scales, codes, B, N, D))
+                td, _ = timeit(lambda: kvq.kvq_dequantize_t(dt, codes, scales, xh, B, N, D))
+                cell = lambda t, bpe: "%.4f (%.0f, %.3f)" % (t, bpe * E / t / 1e6, bpe * E / t / 1e6 / 8000.0)
+                print("| %s | %d x %d x %d | %s | %s | %s |" % (name, B, N, D, cell(ta, 2.0), cell(tq, 3.0), cell(td, 3.0)))
+                sys.stdout.flush()
+                del x, xh, codes
+                torch.cuda.empty_cache()
+        return
 
     if args.scores:
         print("| batch x N x D | Q | mean ms | bytes moved (GB) | GB/s | of 8 TB/s | fp32 TFLOP/s |")

@@ -345,6 +345,60 @@ def test_scores_from_codes(shape, Q):
         assert (err <= scores_bound(D, fast) * mag + 1e-300).all(), (b, float((err / (mag + 1e-300)).max()))
 
 
+# ------------------------------------------------------------------ fp16 / bf16 matrices
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(1, 1024, 64), (1, 4096, 128), (6, 1000, 128), (2, 257, 1000), (1, 19, 4096),
+                                   (1, 300, 8192), (3, 5, 17), (1, 100, 63), (1, 1, 1), (1, 70, 20), (2, 2050, 8)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_sixteen_bit_matrices(shape, fmt):
+    """Scales and codes of an fp16 / bf16 matrix equal those of the widened matrix (oracle); dequantization
+    into the 16-bit format is the fp32 product rounded once, to nearest even.  All bit-exact."""
+    rng = np.random.default_rng(sum(shape) + len(fmt))
+    x32 = make_matrix(rng, *shape)
+    if fmt == "f16":
+        x32 = np.clip(x32, -60000, 60000)
+    x16 = oracle.narrow16(x32, fmt)
+    xw = oracle.widen16(x16, fmt)
+    s_ref = oracle.compute_scales(xw)
+    q_ref = oracle.quantize(xw, s_ref)
+    xh_ref = oracle.dequantize_as(q_ref, s_ref, fmt)
+    dt = kvq.DTYPE_F16 if fmt == "f16" else kvq.DTYPE_BF16
+    batch, N, D = shape
+    n = batch * N * D
+    for offset in (0, 1):     # aligned, and shifted by one element (generic kernels)
+        xd = torch.zeros(n + 16, dtype=torch.int16, device="cuda")
+        xd[offset:offset + n].copy_(torch.from_numpy(x16.view(np.int16).reshape(-1)))
+        scales = torch.full((batch * D + 16,), -5.0, dtype=torch.float32, device="cuda")
+        codes = torch.full((n + 16,), 99, dtype=torch.int8, device="cuda")
+        xh = torch.full((n + 16,), 12345, dtype=torch.int16, device="cuda")
+        sv, cv, hv, xv = scales[offset:], codes[offset:], xh[offset:], xd[offset:]
+        kvq.kvq_absmax_scales_t(dt, xv, sv, batch, N, D)
+        kvq.kvq_quantize_t(dt, xv, sv, cv, batch, N, D)
+        kvq.kvq_dequantize_t(dt, cv, sv, hv, batch, N, D)
+        assert_bits_equal(sv[:batch * D].cpu().numpy().reshape(batch, D), s_ref, "%s scales" % fmt)
+        assert_bits_equal(cv[:n].cpu().numpy().reshape(shape), q_ref, "%s codes" % fmt)
+        got = hv[:n].cpu().numpy().view(np.uint16).reshape(shape)
+        assert np.array_equal(got, xh_ref), "%s x_hat" % fmt
+        assert bool((codes[:offset] == 99).all() and (codes[offset + n:] == 99).all())
+        assert bool((xh[:offset] == 12345).all() and (xh[offset + n:] == 12345).all())
+        assert bool((scales[:offset] == -5.0).all() and (scales[offset + batch * D:] == -5.0).all())
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_quantize_t(7, xd, scales, codes, batch, N, D)
+
+
+def test_typed_calls_forward_fp32():
+    x = W.generate(1)[0]
+    g = Gpu(x)
+    kvq.kvq_absmax_scales_t(kvq.DTYPE_F32, g.x, g.scales, 1, g.N, g.D)
+    kvq.kvq_quantize_t(kvq.DTYPE_F32, g.x, g.scales, g.codes, 1, g.N, g.D)
+    kvq.kvq_dequantize_t(kvq.DTYPE_F32, g.codes, g.scales, g.xh, 1, g.N, g.D)
+    s_ref = oracle.compute_scales(x)
+    q_ref = oracle.quantize(x, s_ref)
+    assert_bits_equal(g.scales.cpu().numpy(), s_ref, "scales")
+    assert_bits_equal(g.codes.cpu().numpy().reshape(g.N, g.D), q_ref, "codes")
+    assert_bits_equal(g.xh.cpu().numpy().reshape(g.N, g.D), oracle.dequantize(q_ref, s_ref), "x_hat")
+
+
 FUSED_SHAPES = [(7, 512, 128), (3, 1000, 64), (2, 16, 4096), (5, 17, 20), (1, 16384, 4), (1, 16385, 4),
                 (4, 2048, 32), (9, 1, 8), (2, 513, 128), (1, 65, 1024), (300, 64, 64)]
 
