@@ -42,6 +42,10 @@ def lib():
             L.kvq_oracle_attn_score_error.restype = None
             L.kvq_oracle_scores_from_codes.argtypes = [_fp, _i64, _bp, _fp, _i64, _i64, _dp]
             L.kvq_oracle_scores_from_codes.restype = None
+            L.kvq_oracle_compute_scales_q.argtypes = [_fp, _fp, _i64, _i64, _i64, ctypes.c_int]
+            L.kvq_oracle_compute_scales_q.restype = None
+            L.kvq_oracle_quantize_q.argtypes = [_fp, _fp, _bp, _i64, _i64, _i64, ctypes.c_int]
+            L.kvq_oracle_quantize_q.restype = None
             _lib = L
     return _lib
 
@@ -173,3 +177,53 @@ def narrow16(x, fmt):
 def dequantize_as(codes, scales, fmt):
     """x_hat = round_to_16bit(float32(code) * scale): Eq. (dequant_op) in fp32, then one rounding."""
     return narrow16(dequantize(codes, scales), fmt)
+
+
+# ---------------------------------------------------------------------------------------------
+# 4-bit codes (Limitations, "Lower bit-widths"): the same method with the range [-7, 7]
+# ---------------------------------------------------------------------------------------------
+def compute_scales_q(x, qmax):
+    """scales[b, d] = max_t |x[b, t, d]| / qmax (fp32)."""
+    x = _f32(x)
+    b, n, d = _shape3(x)
+    out = np.empty((b, d), dtype=np.float32)
+    lib().kvq_oracle_compute_scales_q(_ptr(x, _fp), _ptr(out, _fp), b, n, d, int(qmax))
+    return out if x.ndim == 3 else out[0]
+
+
+def quantize_q(x, scales, qmax):
+    """codes = clamp(rint(x / scale), -qmax, qmax), one code per int8; 0 where scale == 0."""
+    x = _f32(x)
+    scales = _f32(scales)
+    b, n, d = _shape3(x)
+    if scales.size != b * d:
+        raise ValueError("scales must hold batch*D values")
+    out = np.empty(x.shape, dtype=np.int8)
+    lib().kvq_oracle_quantize_q(_ptr(x, _fp), _ptr(scales, _fp), _ptr(out, _bp), b, n, d, int(qmax))
+    return out
+
+
+def pack_int4(codes):
+    """Two 4-bit two's-complement codes per byte: channel 2j in the low nibble, 2j+1 in the high nibble."""
+    codes = np.ascontiguousarray(codes)
+    if codes.dtype != np.int8 or codes.shape[-1] % 2:
+        raise ValueError("expected int8 codes with an even number of channels")
+    if codes.min(initial=0) < -8 or codes.max(initial=0) > 7:
+        raise ValueError("codes do not fit 4 bits")
+    u = codes.view(np.uint8) & np.uint8(0x0F)
+    return (u[..., 0::2] | (u[..., 1::2] << np.uint8(4))).astype(np.uint8)
+
+
+def unpack_int4(packed):
+    """Inverse of pack_int4: uint8 [..., D/2] -> int8 [..., D] with sign extension."""
+    packed = np.ascontiguousarray(packed)
+    if packed.dtype != np.uint8:
+        raise TypeError("expected uint8")
+    lo = (packed & np.uint8(0x0F)).astype(np.int8)
+    hi = (packed >> np.uint8(4)).astype(np.int8)
+    lo = np.where(lo > 7, lo - 16, lo).astype(np.int8)
+    hi = np.where(hi > 7, hi - 16, hi).astype(np.int8)
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.int8)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    return out

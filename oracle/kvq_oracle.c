@@ -167,3 +167,48 @@ void kvq_oracle_scores_from_codes(const float *queries, int64_t Q,
         }
     }
 }
+
+/* The same method at another bit width (Limitations, "Lower bit-widths: INT4 ..."): the integer
+ * range [-127, 127] of Eq. (scale) / Eq. (quant_op) becomes [-qmax, qmax] (qmax = 7 for 4 bits):
+ * scale = absmax / qmax, code = clamp(rint(x / scale), -qmax, qmax).  Codes are returned one per
+ * int8; packing two 4-bit codes into a byte is a storage matter done outside the oracle's C code. */
+void kvq_oracle_compute_scales_q(const float *x, float *scales, int64_t batch, int64_t N, int64_t D, int qmax)
+{
+    const float qm = (float)qmax;
+    for (int64_t b = 0; b < batch; b++) {
+        const float *slab = x + (size_t)b * (size_t)N * (size_t)D;
+        for (int64_t d = 0; d < D; d++) {
+            float max_abs = 0.0f;
+            for (int64_t t = 0; t < N; t++) {
+                float a = fabsf(slab[(size_t)t * (size_t)D + (size_t)d]);
+                if (a > max_abs)
+                    max_abs = a;
+            }
+            scales[(size_t)b * (size_t)D + (size_t)d] = max_abs / qm;
+        }
+    }
+}
+
+void kvq_oracle_quantize_q(const float *x, const float *scales, int8_t *codes,
+                           int64_t batch, int64_t N, int64_t D, int qmax)
+{
+    const float qm = (float)qmax;
+    for (int64_t b = 0; b < batch; b++) {
+        for (int64_t t = 0; t < N; t++) {
+            for (int64_t d = 0; d < D; d++) {
+                size_t i = ((size_t)b * (size_t)N + (size_t)t) * (size_t)D + (size_t)d;
+                float s = scales[(size_t)b * (size_t)D + (size_t)d];
+                int8_t q = 0;
+                if (s != 0.0f) {
+                    float r = rintf(x[i] / s);
+                    if (r > qm)
+                        r = qm;
+                    if (r < -qm)
+                        r = -qm;
+                    q = (int8_t)(int)r;
+                }
+                codes[i] = q;
+            }
+        }
+    }
+}

@@ -435,3 +435,43 @@ def test_dequantize_as_16_bit_rounds_the_fp32_product_once():
         err = np.abs(xw.astype(np.float64) - oracle.widen16(xh16, fmt).astype(np.float64))
         ulp16 = np.abs(xh32.astype(np.float64)) * 2.0 ** (-10 if fmt == "f16" else -7)
         assert (err <= s.astype(np.float64)[None, :] / 2 * (1 + 2.0 ** -15) + ulp16 / 2 + 1e-30).all()
+
+
+# --------------------------------------------------------------------------
+# 4-bit codes
+# --------------------------------------------------------------------------
+def test_int4_hand_worked_and_packing():
+    # column 0: absmax 7 -> s = 1; quotients 7, .5, 1.5, -2.5 -> 7, 0, 2, -2 (ties to even)
+    # column 1: absmax 14 (negative) -> s = 2; -14/2 = -7; 3/2 = 1.5 -> 2; 5/2 = 2.5 -> 2; -1/2 = -.5 -> -0
+    x = np.array([[7.0, -14.0], [0.5, 3.0], [1.5, 5.0], [-2.5, -1.0]], dtype=np.float32)
+    s = oracle.compute_scales_q(x, 7)
+    assert s.tolist() == [1.0, 2.0]
+    q = oracle.quantize_q(x, s, 7)
+    assert q.tolist() == [[7, -7], [0, 2], [2, 2], [-2, 0]]
+    # low nibble = even channel, high nibble = odd channel, two's complement: -7 -> 0x9, -2 -> 0xE
+    packed = oracle.pack_int4(q)
+    assert packed.dtype == np.uint8 and packed.tolist() == [[0x97], [0x20], [0x22], [0x0E]]
+    assert np.array_equal(oracle.unpack_int4(packed), q)
+    assert oracle.dequantize(q, s).tolist() == [[7.0, -14.0], [0.0, 4.0], [2.0, 4.0], [-2.0, 0.0]]
+
+
+def test_int4_against_exact_rationals_and_the_8_bit_functions():
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal((40, 6)) * np.exp(rng.uniform(-2, 2, 6))).astype(np.float32)
+    x[:, 5] = (np.arange(40) - 20) * 0.25
+    x[0, 5] = 7 * 0.5
+    s = oracle.compute_scales_q(x, 7)
+    q = oracle.quantize_q(x, s, 7)
+    for d in range(6):
+        absmax = max(abs(Fraction(float(v))) for v in x[:, d])
+        assert Fraction(float(s[d])) == fl32(absmax / 7)
+        for t in range(40):
+            q32 = fl32(Fraction(float(x[t, d])) / Fraction(float(s[d])))
+            assert int(q[t, d]) == max(-7, min(7, round_half_even(q32)))
+    assert np.abs(q).max() == 7 and (np.abs(q).max(axis=0) == 7).all()
+    # qmax = 127 is the 8-bit method
+    assert np.array_equal(oracle.compute_scales_q(x, 127), oracle.compute_scales(x))
+    assert np.array_equal(oracle.quantize_q(x, oracle.compute_scales(x), 127), oracle.quantize(x, oracle.compute_scales(x)))
+    # error bound of Eq. (error_bound) with the coarser step
+    xh = oracle.dequantize(q, s)
+    assert (np.abs(x.astype(np.float64) - xh) <= s.astype(np.float64)[None, :] / 2 * (1 + 2.0 ** -15)).all()
