@@ -100,6 +100,25 @@ kvq_status kvq_dequantize_t(int dtype, const int8_t *codes, const float *scales,
                             int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
 
 /*
+ * The same method with 4-bit codes -- Limitations, "Lower bit-widths" (INT4 for 8x
+ * compression): the integer range of Eq. (scale) / Eq. (quantize) becomes [-7, 7]:
+ *   scales[b,d]  = max_t |x[b,t,d]| / 7
+ *   code[b,t,d]  = clamp(rint(x[b,t,d] / scales[b,d]), -7, 7), 0 where the scale is 0
+ *   x_hat[b,t,d] = (float)code[b,t,d] * scales[b,d]
+ * with the same fp32 divide, rounding and multiply as the 8-bit calls.  Codes are
+ * stored two per byte in two's complement, channel 2j in the low nibble and channel
+ * 2j+1 in the high nibble of byte j of the row, so D must be even (KVQ_ERR_ARG
+ * otherwise) and packed is [batch, N, D/2] bytes.
+ *   x / x_hat [batch,N,D] fp32, scales [batch,D] fp32, packed [batch,N,D/2] uint8: device
+ */
+kvq_status kvq_absmax_scales_int4(const float *x, float *scales,
+                                  int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+kvq_status kvq_quantize_int4(const float *x, const float *scales, uint8_t *packed,
+                             int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+kvq_status kvq_dequantize_int4(const uint8_t *packed, const float *scales, float *x_hat,
+                               int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
  * Scale computation and quantization in one call (same results as
  * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
  * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in

@@ -28,9 +28,10 @@ __global__ __launch_bounds__(kBlock) void fill_zero_u32(uint32_t* p, int64_t n) 
 }
 
 // One IEEE fp32 divide per channel, in place over the max bit patterns.
-__global__ __launch_bounds__(kBlock) void finalize_scales(float* scales, int64_t n) {
+// qmax = 127 (8-bit codes) or 7 (4-bit codes).
+__global__ __launch_bounds__(kBlock) void finalize_scales(float* scales, int64_t n, float qmax) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n) scales[i] = scales[i] / 127.0f;
+  if (i < n) scales[i] = scales[i] / qmax;
 }
 
 // |v| joins the running maximum only when strictly larger, as in the algorithm;
@@ -143,7 +144,7 @@ static kvq_status launch_absmax_t(const float* x, uint32_t* bits, int64_t N, int
 }
 
 kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
-                                hipStream_t stream) {
+                                hipStream_t stream, float qmax) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options& o = options();
@@ -197,7 +198,7 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   else KVQ_AM(1, 1, 16);
 #undef KVQ_AM
   if (s != KVQ_OK) return s;
-  hipLaunchKernelGGL(finalize_scales, dim3((uint32_t)small_blocks), dim3(kBlock), 0, stream, scales, n_scales);
+  hipLaunchKernelGGL(finalize_scales, dim3((uint32_t)small_blocks), dim3(kBlock), 0, stream, scales, n_scales, qmax);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }

@@ -176,6 +176,29 @@ kvq_status kvq_dequantize_t(int dtype, const int8_t* codes, const float* scales,
   return launch_dequantize_16(dtype, codes, scales, x_hat, batch, N, D, stream);
 }
 
+kvq_status kvq_absmax_scales_int4(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                  kvq_stream_t stream) {
+  if (!x || !scales) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_absmax_scales(x, scales, batch, N, D, stream, 7.0f);
+}
+
+kvq_status kvq_quantize_int4(const float* x, const float* scales, uint8_t* packed, int64_t batch, int64_t N,
+                             int64_t D, kvq_stream_t stream) {
+  if (!x || !scales || !packed) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (D % 2) return KVQ_ERR_ARG;
+  return launch_quantize_int4(x, scales, packed, batch, N, D, stream);
+}
+
+kvq_status kvq_dequantize_int4(const uint8_t* packed, const float* scales, float* x_hat, int64_t batch, int64_t N,
+                               int64_t D, kvq_stream_t stream) {
+  if (!packed || !scales || !x_hat) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (D % 2) return KVQ_ERR_ARG;
+  return launch_dequantize_int4(packed, scales, x_hat, batch, N, D, stream);
+}
+
 kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N,
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;

@@ -85,8 +85,14 @@ struct Workspace {
 kvq_status get_workspace(hipStream_t stream, Workspace* out);
 
 // ---- launchers (each validates nothing: the C-ABI layer has done that) ----
+// scales = column absmax / qmax (127 for 8-bit codes, 7 for 4-bit codes)
 kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
-                                hipStream_t stream);
+                                hipStream_t stream, float qmax = 127.0f);
+// 4-bit codes, two per byte (packed rows of D / 2 bytes); D is even.
+kvq_status launch_quantize_int4(const float* x, const float* scales, uint8_t* packed, int64_t batch, int64_t N,
+                                int64_t D, hipStream_t stream);
+kvq_status launch_dequantize_int4(const uint8_t* packed, const float* scales, float* x_hat, int64_t batch,
+                                  int64_t N, int64_t D, hipStream_t stream);
 kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
                            int64_t D, hipStream_t stream);
 kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch,

@@ -22,6 +22,7 @@ OPT_ABSMAX_BLOCKS_PER_CU = 11
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
 )
@@ -55,6 +56,11 @@ def lib():
         L.kvq_quantize_t.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_dequantize_t.argtypes = [i32, p, p, p, i64, i64, i64, p]
         for name in ("kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t"):
+            getattr(L, name).restype = i32
+        L.kvq_absmax_scales_int4.argtypes = [p, p, i64, i64, i64, p]
+        L.kvq_quantize_int4.argtypes = [p, p, p, i64, i64, i64, p]
+        L.kvq_dequantize_int4.argtypes = [p, p, p, i64, i64, i64, p]
+        for name in ("kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4"):
             getattr(L, name).restype = i32
         L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.restype = i32
@@ -138,6 +144,21 @@ def kvq_quantize_t(dtype, x, scales, codes, batch, N, D, stream=None):
 def kvq_dequantize_t(dtype, codes, scales, x_hat, batch, N, D, stream=None):
     _check(lib().kvq_dequantize_t(dtype, _addr(codes), _addr(scales), _addr(x_hat), batch, N, D, _stream(stream)),
            "kvq_dequantize_t")
+
+
+def kvq_absmax_scales_int4(x, scales, batch, N, D, stream=None):
+    _check(lib().kvq_absmax_scales_int4(_addr(x), _addr(scales), batch, N, D, _stream(stream)),
+           "kvq_absmax_scales_int4")
+
+
+def kvq_quantize_int4(x, scales, packed, batch, N, D, stream=None):
+    _check(lib().kvq_quantize_int4(_addr(x), _addr(scales), _addr(packed), batch, N, D, _stream(stream)),
+           "kvq_quantize_int4")
+
+
+def kvq_dequantize_int4(packed, scales, x_hat, batch, N, D, stream=None):
+    _check(lib().kvq_dequantize_int4(_addr(packed), _addr(scales), _addr(x_hat), batch, N, D, _stream(stream)),
+           "kvq_dequantize_int4")
 
 
 VARIANT_PRODUCTION, VARIANT_NAIVE, VARIANT_TILED, VARIANT_COARSENED, VARIANT_VECTORIZED = 0, 1, 2, 3, 4

@@ -2,6 +2,7 @@
 
 Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
         python -m paper_2601_04719_amd.report --sixteen          (fp16 / bf16 matrices)
+        python -m paper_2601_04719_amd.report --int4             (4-bit codes, two per byte)
         python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
@@ -22,6 +23,7 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--paper-sweep", action="store_true")
     ap.add_argument("--sixteen", action="store_true", help="fp16 / bf16 matrices: absmax, quantize, dequantize")
+    ap.add_argument("--int4", action="store_true", help="4-bit codes: absmax, quantize, dequantize, max-abs error")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
@@ -64,6 +66,36 @@ def main():
                 sys.stdout.flush()
                 del x, xh, codes
                 torch.cuda.empty_cache()
+        return
+
+    if args.int4:
+        print("| workload | absmax/7 ms (GB/s, of 8 TB/s) | quantize ms (GB/s, of 8 TB/s) | dequantize ms (GB/s, of 8 TB/s) "
+              "| max-abs error 4-bit | max-abs error 8-bit |")
+        print("|---|---|---|---|---|---|")
+        sumsq = torch.zeros(1, dtype=torch.float64, device="cuda")
+        maxabs = torch.zeros(1, dtype=torch.float32, device="cuda")
+        for cfg in [int(c) for c in args.configs.split(",")]:
+            c = W.CONFIGS[cfg]
+            B, N, D, E = c.batch, c.N, c.D, c.elements
+            x = torch.from_numpy(W.generate(cfg)).cuda().reshape(-1)
+            scales = torch.empty(B * D, device="cuda")
+            packed = torch.empty(E // 2, dtype=torch.uint8, device="cuda")
+            xh = torch.empty(E, device="cuda")
+            ta, _ = timeit(lambda: kvq.kvq_absmax_scales_int4(x, scales, B, N, D))
+            tq, _ = timeit(lambda: kvq.kvq_quantize_int4(x, scales, packed, B, N, D))
+            td, _ = timeit(lambda: kvq.kvq_dequantize_int4(packed, scales, xh, B, N, D))
+            kvq.kvq_roundtrip_error(x, xh, None, None, B, N, D, sumsq, maxabs)
+            e4 = float(maxabs.item())
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            kvq.kvq_absmax_scales(x, scales, B, N, D)
+            kvq.kvq_quantize(x, scales, codes, B, N, D)
+            kvq.kvq_roundtrip_error(x, None, codes, scales, B, N, D, sumsq, maxabs)
+            e8 = float(maxabs.item())
+            cell = lambda t, bpe: "%.4f (%.0f, %.3f)" % (t, bpe * E / t / 1e6, bpe * E / t / 1e6 / 8000.0)
+            print("| %s | %s | %s | %s | %.4g | %.4g |" % (c.name, cell(ta, 4.0), cell(tq, 4.5), cell(td, 4.5), e4, e8))
+            sys.stdout.flush()
+            del x, xh, packed, codes
+            torch.cuda.empty_cache()
         return
 
     if args.scores:

@@ -534,3 +534,117 @@ def test_works_on_a_non_default_stream():
     xh_ref = oracle.dequantize(q_ref, s_ref)
     ss_ref, mx_ref = oracle.roundtrip_error(x, xh_ref)
     assert float(g.sumsq.item()) == pytest.approx(ss_ref, rel=REL) and np.float32(g.maxabs.item()) == mx_ref
+
+
+# ------------------------------------------------------------------ 4-bit codes
+def int4_round_trip(x, offset=0, given_scales=None):
+    """kvq_*_int4 against the oracle's qmax = 7 functions: scales, packed bytes and x_hat bit-exact,
+    and nothing written outside the buffers."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.ndim == 2:
+        x = x[None]
+    batch, N, D = x.shape
+    n = x.size
+    dx = torch.empty(n + 64, dtype=torch.float32, device="cuda")
+    xs = dx[offset:offset + n]
+    xs.copy_(torch.from_numpy(x.reshape(-1)))
+    ds = torch.full((batch * D + 64,), -5.0, dtype=torch.float32, device="cuda")
+    ss = ds[offset:offset + batch * D]
+    dp = torch.full((n // 2 + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    ps = dp[offset:offset + n // 2]
+    dh = torch.full((n + 64,), 777.0, dtype=torch.float32, device="cuda")
+    hs = dh[offset:offset + n]
+    if given_scales is None:
+        kvq.kvq_absmax_scales_int4(xs, ss, batch, N, D)
+        s_ref = oracle.compute_scales_q(x, 7)
+        assert_bits_equal(ss.cpu().numpy().reshape(batch, D), s_ref, "int4 scales")
+    else:
+        s_ref = np.ascontiguousarray(given_scales, dtype=np.float32).reshape(batch, D)
+        ss.copy_(torch.from_numpy(s_ref.reshape(-1)))
+    kvq.kvq_quantize_int4(xs, ss, ps, batch, N, D)
+    q_ref = oracle.quantize_q(x, s_ref, 7)
+    p_ref = oracle.pack_int4(q_ref)
+    assert_bits_equal(ps.cpu().numpy().reshape(batch, N, D // 2), p_ref, "packed 4-bit codes")
+    kvq.kvq_dequantize_int4(ps, ss, hs, batch, N, D)
+    assert_bits_equal(hs.cpu().numpy().reshape(x.shape), oracle.dequantize(q_ref, s_ref), "int4 x_hat")
+    torch.cuda.synchronize()
+    assert bool((dp[:offset] == 0x5A).all() and (dp[offset + n // 2:] == 0x5A).all())
+    assert bool((dh[:offset] == 777.0).all() and (dh[offset + n:] == 777.0).all())
+    assert bool((ds[:offset] == -5.0).all() and (ds[offset + batch * D:] == -5.0).all())
+    return q_ref
+
+
+INT4_SHAPES = [(1, 1, 2), (1, 3, 6), (1, 64, 16), (3, 5, 18), (1, 100, 62), (2, 33, 66), (1, 300, 128),
+               (2, 257, 1000), (1, 19, 4096), (1, 3, 4100), (1, 3, 4102), (5, 1, 272), (1, 2050, 8), (1, 1024, 64),
+               (1, 4100, 256), (8, 515, 128)]
+
+
+@pytest.mark.parametrize("shape", INT4_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_int4_ragged_shapes(shape):
+    rng = np.random.default_rng(hash(shape) % (1 << 31))
+    x = make_matrix(rng, *shape)
+    if shape[2] >= 6 and shape[1] >= 4:          # exact ties at 4 bits: multiples of s/2 with absmax 7 s
+        s = np.float32(0.5)
+        x[:, :, 4] = (rng.integers(-13, 14, shape[:2]) * (s / 2)).astype(np.float32)
+        x[:, 0, 4] = 7 * s
+    q = int4_round_trip(x)
+    assert np.abs(q).max() <= 7
+
+
+@pytest.mark.parametrize("offset", [1, 2, 3, 4, 8])
+def test_int4_unaligned_base_pointers(offset):
+    rng = np.random.default_rng(offset)
+    int4_round_trip(make_matrix(rng, 2, 70, 64), offset=offset)
+
+
+def test_int4_config2_and_config3_slabs():
+    q = int4_round_trip(W.generate(2)[0])
+    assert set(np.unique(q).tolist()) == set(range(-7, 8))
+    int4_round_trip(W.generate(3, slabs=(0, 40)))
+
+
+def test_int4_ties_clipping_and_special_scales():
+    rng = np.random.default_rng(23)
+    N, D = 4096, 64
+    s = np.exp(rng.uniform(-3, 3, D)).astype(np.float32)
+    s[0], s[1], s[2], s[3], s[4], s[5] = 2.0 ** -140, 2.0 ** 120, 1e-3, 3.0, 0.0, -0.25
+    k = rng.integers(-9, 10, (N, D)).astype(np.float64) + 0.5
+    x = (k * s.astype(np.float64)).astype(np.float32)
+    x[::3] = np.nextafter(x[::3], np.float32(np.inf))
+    x[1::3] = np.nextafter(x[1::3], np.float32(-np.inf))
+    x[:, 0] = (rng.integers(-20, 20, N) * 2.0 ** -141).astype(np.float32)
+    x[:, 1] = (rng.standard_normal(N) * 2.0 ** 125).astype(np.float32)
+    int4_round_trip(x, given_scales=s)
+
+
+def test_int4_rejects_an_odd_channel_count():
+    x = torch.zeros(15, dtype=torch.float32, device="cuda")
+    s = torch.zeros(5, dtype=torch.float32, device="cuda")
+    p = torch.zeros(8, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.kvq_quantize_int4(x, s, p, 1, 3, 5)
+    assert e.value.status == kvq.ERR_ARG
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.kvq_dequantize_int4(p, s, x, 1, 3, 5)
+    assert e.value.status == kvq.ERR_ARG
+
+
+def test_int4_full_size_sampled_rows():
+    """The 1B-element configuration in the launch shape the report times: scales of the whole matrix
+    against the oracle, packed codes and x_hat on sampled row blocks."""
+    c = W.CONFIGS[5]
+    x = W.generate(5)[0]
+    s_ref = oracle.compute_scales_q(x, 7)
+    dx = torch.from_numpy(x).cuda()
+    ds = torch.empty(c.D, dtype=torch.float32, device="cuda")
+    dp = torch.empty((c.N, c.D // 2), dtype=torch.uint8, device="cuda")
+    dh = torch.empty((c.N, c.D), dtype=torch.float32, device="cuda")
+    kvq.kvq_absmax_scales_int4(dx, ds, 1, c.N, c.D)
+    assert_bits_equal(ds.cpu().numpy(), s_ref, "int4 scales of the full matrix")
+    kvq.kvq_quantize_int4(dx, ds, dp, 1, c.N, c.D)
+    kvq.kvq_dequantize_int4(dp, ds, dh, 1, c.N, c.D)
+    rows = 4096
+    for r0 in (0, 37 * rows + 5, c.N - rows):
+        q_ref = oracle.quantize_q(x[r0:r0 + rows], s_ref, 7)
+        assert_bits_equal(dp[r0:r0 + rows].cpu().numpy(), oracle.pack_int4(q_ref), "packed rows %d" % r0)
+        assert_bits_equal(dh[r0:r0 + rows].cpu().numpy(), oracle.dequantize(q_ref, s_ref), "x_hat rows %d" % r0)
