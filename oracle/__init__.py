@@ -227,3 +227,35 @@ def unpack_int4(packed):
     out[..., 0::2] = lo
     out[..., 1::2] = hi
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Streaming append (Limitations, "Dynamic quantization": scales that adapt during inference;
+# Future Work: streaming workloads).  The cache keeps only codes and scales, so when new tokens
+# raise a channel's absmax the cached codes of that channel are re-expressed in the new scale
+# from their reconstruction:  code' = Q(code * s_old ; s_new), with Q and the product being
+# Eq. (quant_op) and Eq. (dequant_op).  Built from the functions above, nothing else.
+# ---------------------------------------------------------------------------------------------
+def append(codes, scales, n_old, x_new):
+    """codes [batch, capacity, D] int8 (rows [0, n_old) valid), scales [batch, D], x_new [batch, m, D].
+
+    Returns (codes', scales', scales_prev): rows [0, n_old + m) of codes' valid, the rest untouched."""
+    codes = np.ascontiguousarray(codes)
+    x_new = _f32(x_new)
+    if codes.ndim != 3 or x_new.ndim != 3 or codes.dtype != np.int8:
+        raise ValueError("expected codes [batch, capacity, D] int8 and x_new [batch, m, D] float32")
+    batch, cap, D = codes.shape
+    m = x_new.shape[1]
+    s_old = _f32(scales).reshape(batch, D)
+    if x_new.shape[0] != batch or x_new.shape[2] != D or not (0 <= n_old and n_old + m <= cap):
+        raise ValueError("shape mismatch or capacity exceeded")
+    cand = compute_scales(x_new).reshape(batch, D)                 # absmax of the new tokens / 127
+    s_new = np.where(cand > s_old, cand, s_old).astype(np.float32)
+    grew = s_new > s_old                                           # [batch, D]
+    out = codes.copy()
+    if n_old:
+        cached = np.ascontiguousarray(codes[:, :n_old])
+        again = quantize(dequantize(cached, s_old), s_new)         # reconstruction, then the new scale
+        out[:, :n_old] = np.where(grew[:, None, :], again, cached)
+    out[:, n_old:n_old + m] = quantize(x_new, s_new)
+    return out, s_new, s_old.copy()

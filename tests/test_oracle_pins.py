@@ -475,3 +475,57 @@ def test_int4_against_exact_rationals_and_the_8_bit_functions():
     # error bound of Eq. (error_bound) with the coarser step
     xh = oracle.dequantize(q, s)
     assert (np.abs(x.astype(np.float64) - xh) <= s.astype(np.float64)[None, :] / 2 * (1 + 2.0 ** -15)).all()
+
+
+# --------------------------------------------------------------------------
+# streaming append
+# --------------------------------------------------------------------------
+def test_append_hand_worked_growth_and_no_growth():
+    # channel 0 grows 1 -> 2: cached 127, 64, 3, -1, 0 become 127/2 = 63.5 -> 64 (tie to even), 32,
+    # 1.5 -> 2, -0.5 -> 0, 0; the new token 254 gets code 127.  Channel 1 (scale 0.5) does not grow:
+    # its codes stay, and the new token 10 gets 10 / 0.5 = 20.
+    cache = np.zeros((1, 8, 2), dtype=np.int8)
+    cache[0, :5, 0] = [127, 64, 3, -1, 0]
+    cache[0, :5, 1] = [127, -5, 1, 0, 77]
+    cache[0, 5:] = 99                                      # beyond the valid rows: must stay
+    s = np.array([[1.0, 0.5]], dtype=np.float32)
+    x_new = np.array([[[254.0, 10.0]]], dtype=np.float32)
+    out, s_new, prev = oracle.append(cache, s, 5, x_new)
+    assert s_new.tolist() == [[2.0, 0.5]] and prev.tolist() == [[1.0, 0.5]]
+    assert out[0, :6, 0].tolist() == [64, 32, 2, 0, 0, 127]
+    assert out[0, :6, 1].tolist() == [127, -5, 1, 0, 77, 20]
+    assert (out[0, 6:] == 99).all()
+
+
+def test_append_from_empty_equals_batch_and_scales_track_the_running_absmax():
+    rng = np.random.default_rng(41)
+    B, N, D = 2, 96, 10
+    x = (rng.standard_normal((B, N, D)) * np.exp(rng.uniform(-2, 2, (B, 1, D)))).astype(np.float32)
+    x[:, :, 3] *= np.linspace(0.1, 3.0, N)[None, :]          # a channel whose absmax keeps growing
+    x[:, 0, 4] = 50.0                                         # a channel fixed by its first token
+    x[:, :, 5] = 0.0                                          # an all-zero channel
+    cache = np.full((B, 128, D), 55, dtype=np.int8)
+    s = np.zeros((B, D), dtype=np.float32)
+    # one append of everything onto an empty cache is the batch method
+    out, s1, _ = oracle.append(cache, s, 0, x)
+    assert np.array_equal(s1, oracle.compute_scales(x))
+    assert np.array_equal(out[:, :N], oracle.quantize(x, s1)) and (out[:, N:] == 55).all()
+    # token chunks of mixed sizes
+    n, grow_events = 0, np.zeros((B, D), dtype=np.int64)
+    for m in (1, 1, 6, 24, 1, 31, 32):
+        cache, s_next, prev = oracle.append(cache, s, n, x[:, n:n + m])
+        assert np.array_equal(prev, s)
+        grow_events += (s_next > s) & (n > 0)
+        s, n = s_next, n + m
+        assert np.array_equal(s, oracle.compute_scales(x[:, :n]))        # max and /127 commute
+    assert n == N and (cache[:, N:] == 55).all()
+    batch_codes = oracle.quantize(x, s)
+    never_grew = grow_events == 0
+    assert never_grew[:, 4].all() and never_grew[:, 5].all() and not never_grew[:, 3].any()
+    same = cache[:, :N] == batch_codes
+    assert same[np.broadcast_to(never_grew[:, None, :], same.shape)].all()
+    # every growth adds at most one more half step of the then-current (<= final) scale
+    err = np.abs(x.astype(np.float64) - oracle.dequantize(np.ascontiguousarray(cache[:, :N]), s))
+    bound = (grow_events + 1)[:, None, :] * s.astype(np.float64)[:, None, :] / 2 * (1 + 2.0 ** -15)
+    assert (err <= bound).all()
+    assert (np.abs(cache[:, :N].astype(np.int32)) <= 127).all()
