@@ -119,6 +119,31 @@ kvq_status kvq_dequantize_int4(const uint8_t *packed, const float *scales, float
                                int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
 
 /*
+ * Streaming append -- Limitations, "Dynamic quantization" (scales that adapt during
+ * inference) and Future Work (streaming workloads), with the operations of Eq. (scale),
+ * Eq. (quant_op) and Eq. (dequant_op).  A cache of n_old tokens exists only as int8
+ * codes and per-channel scales; m new fp32 tokens join it:
+ *   cand[b,d]  = max_t |x_new[b,t,d]| / 127
+ *   s_new[b,d] = cand > s_old ? cand : s_old        (so scales track the running absmax)
+ *   channels with s_new > s_old, cached tokens t < n_old:
+ *       codes[b,t,d] <- clamp(rint(((float)codes[b,t,d] * s_old) / s_new), -127, 127)
+ *       (the code is re-expressed from its reconstruction; the fp32 original is gone, so
+ *        each growth of a channel can add up to s_new/2 to the error of its cached tokens)
+ *   new tokens: codes[b,n_old+t,d] = clamp(rint(x_new[b,t,d] / s_new), -127, 127), 0 if s_new == 0
+ * Channels that did not grow keep their codes bit for bit; rows >= n_old + m are not touched.
+ *   x_new       [batch,m,D] fp32, device, read only
+ *   scales      [batch,D] fp32, device: s_old on entry (all 0 for an empty cache), s_new on return
+ *   scales_prev [batch,D] fp32, device, written: s_old (also used as scratch during the call);
+ *               must not overlap scales
+ *   codes       [batch,capacity,D] int8, device: rows [0,n_old) read and possibly rewritten,
+ *               rows [n_old,n_old+m) written
+ * n_old >= 0, m >= 1, n_old + m <= capacity (KVQ_ERR_SHAPE / KVQ_ERR_ARG otherwise).
+ */
+kvq_status kvq_append(const float *x_new, float *scales, float *scales_prev, int8_t *codes,
+                      int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D,
+                      kvq_stream_t stream);
+
+/*
  * Scale computation and quantization in one call (same results as
  * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
  * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in
@@ -242,6 +267,8 @@ int kvq_last_hip_error(void);
  *                           row (1, 2, 4 or 8; capped so that a workgroup spans at most a row)
  *   KVQ_OPT_ABSMAX_BLOCKS_PER_CU  target workgroups per compute unit of the absmax reduction
  *                           when ABSMAX_PASSES is 0: 1..64
+ *   KVQ_OPT_APPEND_BLOCKS_PER_CU  target workgroups per compute unit of the requantization
+ *                           pass of kvq_append (its row chunking): 1..1024
  */
 #define KVQ_OPT_CODEC_WIDTH 1
 #define KVQ_OPT_CODEC_UNROLL 2
@@ -253,6 +280,7 @@ int kvq_last_hip_error(void);
 #define KVQ_OPT_ABSMAX_PASSES 9
 #define KVQ_OPT_ABSMAX_SPAN 10
 #define KVQ_OPT_ABSMAX_BLOCKS_PER_CU 11
+#define KVQ_OPT_APPEND_BLOCKS_PER_CU 12
 kvq_status kvq_set_option(int key, int value);
 int kvq_get_option(int key);
 

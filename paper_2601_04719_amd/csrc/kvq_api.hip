@@ -199,6 +199,16 @@ kvq_status kvq_dequantize_int4(const uint8_t* packed, const float* scales, float
   return launch_dequantize_int4(packed, scales, x_hat, batch, N, D, stream);
 }
 
+kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
+                      int64_t n_old, int64_t m, int64_t capacity, int64_t D, kvq_stream_t stream) {
+  if (!x_new || !scales || !scales_prev || !codes) return KVQ_ERR_NULL;
+  if (n_old < 0 || m < 1) return KVQ_ERR_SHAPE;
+  if (kvq_status s = check_shape(batch, capacity, D)) return s;
+  if (m > capacity || n_old > capacity - m) return KVQ_ERR_ARG;
+  if (scales == scales_prev) return KVQ_ERR_ARG;
+  return launch_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
+}
+
 kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N,
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;
@@ -307,6 +317,10 @@ kvq_status kvq_set_option(int key, int value) {
       if (value < 1 || value > 64) return KVQ_ERR_ARG;
       o.absmax_blocks_per_cu = value;
       return KVQ_OK;
+    case KVQ_OPT_APPEND_BLOCKS_PER_CU:
+      if (value < 1 || value > 1024) return KVQ_ERR_ARG;
+      o.append_blocks_per_cu = value;
+      return KVQ_OK;
     case KVQ_OPT_ABSMAX_SPAN:
       if (value != 1 && value != 2 && value != 4 && value != 8) return KVQ_ERR_ARG;
       o.absmax_span = value;
@@ -329,6 +343,7 @@ int kvq_get_option(int key) {
     case KVQ_OPT_ABSMAX_PASSES: return o.absmax_passes;
     case KVQ_OPT_ABSMAX_SPAN: return o.absmax_span;
     case KVQ_OPT_ABSMAX_BLOCKS_PER_CU: return o.absmax_blocks_per_cu;
+    case KVQ_OPT_APPEND_BLOCKS_PER_CU: return o.append_blocks_per_cu;
     default: return INT_MIN;
   }
 }

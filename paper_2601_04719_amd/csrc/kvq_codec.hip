@@ -75,7 +75,9 @@ __global__ __launch_bounds__(kMaxBlock) void quantize_kernel(const float* __rest
                                                           const float* __restrict__ scales,
                                                           int8_t* __restrict__ codes, int64_t N, int64_t D,
                                                           int tx_log2, uint32_t ctiles, uint32_t rchunks,
-                                                          int64_t rows_per_chunk, int64_t groups) {
+                                                          int64_t rows_per_chunk, int64_t groups,
+                                                          int64_t x_slab, int64_t c_slab) {
+  // x_slab / c_slab: elements between consecutive slabs of x and of codes (N * D when both are dense)
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * V;
@@ -95,8 +97,8 @@ __global__ __launch_bounds__(kMaxBlock) void quantize_kernel(const float* __rest
   }
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
-  const float* px = x + (it.slab * N + row) * D + col;
-  int8_t* pc = codes + (it.slab * N + row) * D + col;
+  const float* px = x + it.slab * x_slab + row * D + col;
+  int8_t* pc = codes + it.slab * c_slab + row * D + col;
 
   if constexpr (V >= 4) {
     typedef typename CodeVec<V>::type cvec;
@@ -212,14 +214,14 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_kernel(const int8_t* __r
 // ----------------------------------------------------------------- launchers
 template <int V, int U>
 static kvq_status launch_q(const float* x, const float* scales, int8_t* codes, int64_t N, int64_t D,
-                           const Tiling& t, bool nt, hipStream_t stream) {
+                           const Tiling& t, bool nt, hipStream_t stream, int64_t x_slab, int64_t c_slab) {
   const dim3 grid((uint32_t)t.items), block(t.block);
   if (nt)
     hipLaunchKernelGGL((quantize_kernel<V, U, true>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
-                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, x_slab, c_slab);
   else
     hipLaunchKernelGGL((quantize_kernel<V, U, false>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
-                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, x_slab, c_slab);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }
@@ -278,12 +280,18 @@ static kvq_status codec_tiling(int64_t batch, int64_t N, int64_t D, const void* 
 
 kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
                            int64_t D, hipStream_t stream) {
+  return launch_quantize_strided(x, scales, codes, batch, N, D, N * D, N * D, stream);
+}
+
+kvq_status launch_quantize_strided(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                                   int64_t D, int64_t x_slab, int64_t c_slab, hipStream_t stream) {
   int U;
   Tiling t;
+  // both slab pitches are multiples of D, so the alignment of row 0 of slab 0 decides for all rows
   if (kvq_status s = codec_tiling(batch, N, D, x, codes, scales, 4, 512, &U, &t)) return s;
   const bool nt = options().nontemporal != 0;
   return dispatch_vu(t.V, U, [&](auto v, auto u) {
-    return launch_q<decltype(v)::value, decltype(u)::value>(x, scales, codes, N, D, t, nt, stream);
+    return launch_q<decltype(v)::value, decltype(u)::value>(x, scales, codes, N, D, t, nt, stream, x_slab, c_slab);
   });
 }
 
@@ -309,7 +317,8 @@ kvq_status launch_probe_codec(int mode, const float* src_f32, float* dst_f32, co
     if (kvq_status s = codec_tiling(batch, N, D, src_f32, dst_i8, scales, 4, 512, &U, &t)) return s;
     if (t.V != 4 || U != 4) return KVQ_ERR_ARG;
     hipLaunchKernelGGL((quantize_kernel<4, 4, true, false>), dim3((uint32_t)t.items), dim3(t.block), 0, stream,
-                       src_f32, scales, dst_i8, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+                       src_f32, scales, dst_i8, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups,
+                       N * D, N * D);
   } else {
     if (kvq_status s = codec_tiling(batch, N, D, dst_f32, src_i8, scales, 2, 256, &U, &t)) return s;
     if (t.V != 4 || U != 2) return KVQ_ERR_ARG;

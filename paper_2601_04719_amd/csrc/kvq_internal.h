@@ -52,6 +52,7 @@ struct Options {
   int absmax_blocks_per_cu = 1;
   int absmax_span = 8;    // column groups per lane (1, 2, 4, 8), capped by the row width
   int absmax_passes = 0;  // 0 = long row chunks sized from blocks_per_cu
+  int append_blocks_per_cu = 32;  // row chunking of the requantization pass of kvq_append
 };
 Options& options();
 
@@ -95,6 +96,13 @@ kvq_status launch_dequantize_int4(const uint8_t* packed, const float* scales, fl
                                   int64_t N, int64_t D, hipStream_t stream);
 kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
                            int64_t D, hipStream_t stream);
+// The same with separate slab pitches (in elements, multiples of D) for x and codes.
+kvq_status launch_quantize_strided(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
+                                   int64_t D, int64_t x_slab, int64_t c_slab, hipStream_t stream);
+// Streaming append: merge the new tokens' absmax into the scales, re-express cached codes of grown
+// channels, quantize the new tokens behind them.
+kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
+                         int64_t n_old, int64_t m, int64_t capacity, int64_t D, hipStream_t stream);
 kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch,
                              int64_t N, int64_t D, hipStream_t stream);
 // One-pass absmax + quantize for slabs that fit one workgroup's registers.

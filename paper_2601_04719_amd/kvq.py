@@ -18,11 +18,12 @@ ERR_NULL, ERR_SHAPE, ERR_OVERFLOW, ERR_HIP, ERR_ARG = -1, -2, -3, -4, -5
 OPT_CODEC_WIDTH, OPT_CODEC_UNROLL, OPT_BLOCKS_PER_CU, OPT_NONTEMPORAL = 1, 2, 3, 4
 OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES, OPT_ABSMAX_SPAN = 6, 7, 8, 9, 10
 OPT_ABSMAX_BLOCKS_PER_CU = 11
+OPT_APPEND_BLOCKS_PER_CU = 12
 
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
-    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
 )
@@ -62,6 +63,8 @@ def lib():
         L.kvq_dequantize_int4.argtypes = [p, p, p, i64, i64, i64, p]
         for name in ("kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4"):
             getattr(L, name).restype = i32
+        L.kvq_append.argtypes = [p, p, p, p, i64, i64, i64, i64, i64, p]
+        L.kvq_append.restype = i32
         L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.restype = i32
         L.kvq_scores_from_codes.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
@@ -159,6 +162,11 @@ def kvq_quantize_int4(x, scales, packed, batch, N, D, stream=None):
 def kvq_dequantize_int4(packed, scales, x_hat, batch, N, D, stream=None):
     _check(lib().kvq_dequantize_int4(_addr(packed), _addr(scales), _addr(x_hat), batch, N, D, _stream(stream)),
            "kvq_dequantize_int4")
+
+
+def kvq_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):
+    _check(lib().kvq_append(_addr(x_new), _addr(scales), _addr(scales_prev), _addr(codes), batch, n_old, m,
+                            capacity, D, _stream(stream)), "kvq_append")
 
 
 VARIANT_PRODUCTION, VARIANT_NAIVE, VARIANT_TILED, VARIANT_COARSENED, VARIANT_VECTORIZED = 0, 1, 2, 3, 4

@@ -3,6 +3,7 @@
 Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
         python -m paper_2601_04719_amd.report --sixteen          (fp16 / bf16 matrices)
         python -m paper_2601_04719_amd.report --int4             (4-bit codes, two per byte)
+        python -m paper_2601_04719_amd.report --append           (streaming append onto an int8 cache)
         python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
@@ -24,6 +25,7 @@ def main():
     ap.add_argument("--paper-sweep", action="store_true")
     ap.add_argument("--sixteen", action="store_true", help="fp16 / bf16 matrices: absmax, quantize, dequantize")
     ap.add_argument("--int4", action="store_true", help="4-bit codes: absmax, quantize, dequantize, max-abs error")
+    ap.add_argument("--append", action="store_true", help="kvq_append: decode steps and prefill chunks")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
@@ -66,6 +68,43 @@ def main():
                 sys.stdout.flush()
                 del x, xh, codes
                 torch.cuda.empty_cache()
+        return
+
+    if args.append:
+        print("| cache batch x capacity x D | new tokens m | slabs (batch > 1) or channels (batch = 1) that grow | "
+              "channels grown | mean ms | min ms |")
+        print("|---|---|---|---|---|---|")
+        for (B, cap, D, m) in [(2048, 4096, 128, 1), (256, 4096, 128, 1), (32, 131072, 128, 1), (1, 131072, 8192, 1),
+                               (2048, 4096, 128, 16), (2048, 4096, 128, 512), (1, 131072, 8192, 1024)]:
+            n_old = cap - m
+            codes = torch.randint(-127, 128, (B * cap * D,), dtype=torch.int8, device="cuda")
+            scales0 = torch.rand(B * D, device="cuda") + 1.0
+            scales = scales0.clone()
+            prev = torch.empty_like(scales)
+            for frac in (0.0, 0.01, 1.0):
+                # new tokens stay inside half the current range; in a fraction of the slabs (of the channels
+                # when there is one slab) they reach twice the range, so those scales grow
+                x = (torch.rand(B, m, D, device="cuda") - 0.5) * 127 * scales0.view(B, 1, D)
+                if frac > 0:
+                    if B > 1:
+                        x[:max(1, int(round(frac * B)))] *= 4
+                    else:
+                        x[:, :, :max(1, int(frac * D))] *= 4
+                x = x.contiguous()
+
+                def step():
+                    scales.copy_(scales0)          # every timed call starts from the same cache state
+                    kvq.kvq_append(x, scales, prev, codes, B, n_old, m, cap, D)
+
+                mean, mn = timeit(step)
+                tc, _ = timeit(lambda: scales.copy_(scales0))
+                step()
+                grown = int((scales > scales0).sum().item())
+                print("| %d x %d x %d | %d | %.0f %% | %d | %.4f | %.4f |" % (B, cap, D, m, 100 * frac, grown,
+                                                                           mean - tc, mn - tc))
+                sys.stdout.flush()
+            del codes
+            torch.cuda.empty_cache()
         return
 
     if args.int4:

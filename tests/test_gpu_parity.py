@@ -648,3 +648,126 @@ def test_int4_full_size_sampled_rows():
         q_ref = oracle.quantize_q(x[r0:r0 + rows], s_ref, 7)
         assert_bits_equal(dp[r0:r0 + rows].cpu().numpy(), oracle.pack_int4(q_ref), "packed rows %d" % r0)
         assert_bits_equal(dh[r0:r0 + rows].cpu().numpy(), oracle.dequantize(q_ref, s_ref), "x_hat rows %d" % r0)
+
+
+# ------------------------------------------------------------------ streaming append
+class GpuCache:
+    """A device cache [batch, capacity, D] of codes + scales, driven through kvq_append."""
+
+    def __init__(self, batch, capacity, D, offset=0):
+        self.batch, self.cap, self.D, self.offset = batch, capacity, D, offset
+        n = batch * capacity * D
+        self._codes = torch.full((n + 64,), 55, dtype=torch.int8, device="cuda")
+        self.codes = self._codes[offset:offset + n]
+        self._scales = torch.full((batch * D + 64,), -5.0, dtype=torch.float32, device="cuda")
+        self.scales = self._scales[offset:offset + batch * D]
+        self.scales.zero_()
+        self._prev = torch.full((batch * D + 64,), -6.0, dtype=torch.float32, device="cuda")
+        self.prev = self._prev[offset:offset + batch * D]
+        self.n = 0
+
+    def append(self, x_np):
+        x_np = np.ascontiguousarray(x_np, dtype=np.float32)
+        m = x_np.shape[1]
+        buf = torch.empty(x_np.size + 64, dtype=torch.float32, device="cuda")
+        xs = buf[self.offset:self.offset + x_np.size]
+        xs.copy_(torch.from_numpy(x_np.reshape(-1)))
+        kvq.kvq_append(xs, self.scales, self.prev, self.codes, self.batch, self.n, m, self.cap, self.D)
+        self.n += m
+
+    def state(self):
+        return (self.codes.cpu().numpy().reshape(self.batch, self.cap, self.D),
+                self.scales.cpu().numpy().reshape(self.batch, self.D),
+                self.prev.cpu().numpy().reshape(self.batch, self.D))
+
+    def guards_intact(self):
+        o, n, ns = self.offset, self.batch * self.cap * self.D, self.batch * self.D
+        return bool((self._codes[:o] == 55).all() and (self._codes[o + n:] == 55).all() and
+                    (self._scales[:o] == -5.0).all() and (self._scales[o + ns:] == -5.0).all() and
+                    (self._prev[:o] == -6.0).all() and (self._prev[o + ns:] == -6.0).all())
+
+
+def growing_tokens(rng, batch, N, D):
+    """Channels 0.. grow at different moments; channel 1 is zero, channel 4 is fixed by its first token."""
+    x = make_matrix(rng, batch, N, D)
+    ramp = np.linspace(0.2, 3.0, N)[None, :]
+    x[:, :, 0] *= ramp
+    if D >= 8:
+        x[:, :, 7] *= ramp ** 2
+        x[:, :, 4] = rng.uniform(-1, 1, (batch, N))
+        x[:, 0, 4] = 2.0
+    if N > 40:
+        x[0, 40, D - 1] = 1e4                    # one late outlier: a single growth event in slab 0
+    return x
+
+
+APPEND_CASES = [((1, 64, 64), (1, 1, 1, 5, 16, 17, 23)), ((3, 300, 128), (17, 1, 100, 1, 1, 64, 116)),
+                ((2, 40, 20), (1, 16, 1, 22)), ((1, 33, 3), (1, 1, 31)), ((2, 50, 65), (20, 1, 29)),
+                ((4, 2100, 256), (2048, 1, 1, 50)), ((1, 9, 4100), (1, 3, 5)), ((6, 48, 8), (48,))]
+
+
+@pytest.mark.parametrize("shape,chunks", APPEND_CASES, ids=lambda v: "x".join(map(str, v)))
+@pytest.mark.parametrize("offset", [0, 1])
+def test_streaming_append_matches_oracle(shape, chunks, offset):
+    batch, cap, D = shape
+    rng = np.random.default_rng(hash((shape, offset)) % (1 << 31))
+    N = sum(chunks)
+    assert N <= cap
+    x = growing_tokens(rng, batch, N, D)
+    g = GpuCache(batch, cap, D, offset)
+    ref_codes = np.full((batch, cap, D), 55, dtype=np.int8)
+    ref_scales = np.zeros((batch, D), dtype=np.float32)
+    n, grown_total = 0, 0
+    for m in chunks:
+        g.append(x[:, n:n + m])
+        ref_codes, new_scales, ref_prev = oracle.append(ref_codes, ref_scales, n, x[:, n:n + m])
+        grown_total += int(((new_scales > ref_scales) & (n > 0)).sum())
+        ref_scales, n = new_scales, n + m
+        codes, scales, prev = g.state()
+        assert_bits_equal(scales, ref_scales, "scales after %d tokens" % n)
+        assert_bits_equal(prev, ref_prev, "previous scales after %d tokens" % n)
+        assert_bits_equal(codes, ref_codes, "cache after %d tokens" % n)
+    assert g.guards_intact()
+    assert_bits_equal(ref_scales, oracle.compute_scales(x), "running scales = batch scales")
+    if len(chunks) > 1:
+        assert grown_total > 0            # the requantization path was exercised
+
+
+def test_streaming_append_decode_step_on_a_full_size_cache():
+    """[256 x 4096 x 128] (config 3's cache), 4095 tokens in place, one more arrives: a few slabs
+    grow, most do not; whole cache against the oracle."""
+    c = W.CONFIGS[3]
+    x = W.generate(3)
+    n_old = c.N - 1
+    s_old = oracle.compute_scales(x[:, :n_old])
+    cache = np.full((c.batch, c.N, c.D), 55, dtype=np.int8)
+    cache[:, :n_old] = oracle.quantize(np.ascontiguousarray(x[:, :n_old]), s_old)
+    tok = np.ascontiguousarray(x[:, n_old:])
+    tok[3, 0, 5] = 4 * s_old[3, 5] * 127            # planted growth: one channel in slab 3,
+    tok[200, 0, :] = -2 * s_old[200] * 127          # and every channel of slab 200
+    g = GpuCache(c.batch, c.N, c.D)
+    g.codes.copy_(torch.from_numpy(cache.reshape(-1)))
+    g.scales.copy_(torch.from_numpy(s_old.reshape(-1)))
+    g.n = n_old
+    g.append(tok)
+    ref_codes, ref_scales, ref_prev = oracle.append(cache, s_old, n_old, tok)
+    codes, scales, prev = g.state()
+    assert_bits_equal(scales, ref_scales, "scales")
+    assert_bits_equal(prev, ref_prev, "previous scales")
+    assert_bits_equal(codes, ref_codes, "cache")
+    grew = ref_scales > s_old
+    assert grew[3, 5] and grew[200].all() and grew.sum() < 0.2 * grew.size
+
+
+def test_streaming_append_argument_errors():
+    g = GpuCache(1, 8, 4)
+    x = torch.zeros(4 * 4, dtype=torch.float32, device="cuda")
+    for args, status in ((dict(n_old=6, m=3), kvq.ERR_ARG), (dict(n_old=-1, m=1), kvq.ERR_SHAPE),
+                         (dict(n_old=0, m=0), kvq.ERR_SHAPE), (dict(n_old=0, m=9), kvq.ERR_ARG)):
+        with pytest.raises(kvq.KvqError) as e:
+            kvq.kvq_append(x, g.scales, g.prev, g.codes, 1, args["n_old"], args["m"], 8, 4)
+        assert e.value.status == status
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.kvq_append(x, g.scales, g.scales, g.codes, 1, 0, 1, 8, 4)
+    assert e.value.status == kvq.ERR_ARG
+    assert bool((g.codes == 55).all())
