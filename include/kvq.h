@@ -212,14 +212,21 @@ kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
  * (the raw dot products q.k, no 1/sqrt(d), no softmax) with k replaced by the
  * reconstruction of Eq. (dequant_op):
  *   scores_out[b,j,t] = sum_d queries[b,j,d] * ((float)codes[b,t,d] * scales[b,d])
- * evaluated in fp32 with the scale folded into the query (q*s, then an FMA per
- * code).  Against exact arithmetic the result is within
- *   (16*ceil(D/1024) + 12) * 2^-24 * sum_d |queries * codes * scales|
- * (generic kernel: (D + 4) * 2^-24 * the same sum).
+ * The scale is folded into the query (qs = q*s, one fp32 rounding) and the codes are
+ * used as read.  Two forms, chosen by shape:
+ *  - Q >= 3, D % 64 == 0, D <= 1024, 16-byte aligned codes: int8 matrix cores.  qs is
+ *    taken to 28-bit fixed point relative to the largest |qs| of its query, the integer
+ *    dot products are exact, the result is rounded once to fp32.  Against exact
+ *    arithmetic: 2^-27 * max_d|queries*scales| * sum_d|codes|
+ *                + 4 * 2^-24 * sum_d |queries * codes * scales|.
+ *    Independent of launch shape and accumulation order.
+ *  - otherwise fp32 FMAs: (16*ceil(D/1024) + 12) * 2^-24 * sum_d |queries * codes * scales|
+ *    for D % 16 == 0 with 16-byte aligned inputs, (D + 4) * 2^-24 * the same sum for the
+ *    generic kernel.
+ *  Where q*s or the score falls below 2^-126 (fp32 gradual underflow) add (127 D + 1) * 2^-150.
  *   queries [batch,Q,D] fp32, codes [batch,N,D] int8, scales [batch,D] fp32:
  *   device, read only.  scores_out [batch,Q,N] fp32: device, written.
- * Any Q >= 1; 8 queries are handled per pass over the codes.  D % 16 == 0 with
- * 16-byte aligned inputs takes the fast kernel, anything else a generic one.
+ * Any Q >= 1; 8 queries (16 on the matrix cores for D <= 512) are handled per pass over the codes.
  */
 kvq_status kvq_scores_from_codes(const float *queries, int64_t Q, const int8_t *codes,
                                  const float *scales, int64_t batch, int64_t N, int64_t D,

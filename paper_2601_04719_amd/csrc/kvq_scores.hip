@@ -206,6 +206,9 @@ static void launch_scores_q(const float* queries, const int8_t* codes, const flo
 
 kvq_status launch_scores_from_codes(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
                                     int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream) {
+  // several queries per head: the int8 matrix-core kernel (no per-code vector ALU work)
+  if (scores_mfma_applicable(queries, Q, codes, scales, D))
+    return launch_scores_mfma(queries, Q, codes, scales, batch, N, D, out, stream);
   const bool fast = D % 16 == 0 && aligned(queries, 16) && aligned(codes, 16) && aligned(scales, 16);
   if (!fast) {
     const int64_t total = batch * Q * N;

@@ -138,19 +138,21 @@ def main():
         return
 
     if args.scores:
-        print("| batch x N x D | Q | mean ms | bytes moved (GB) | GB/s | of 8 TB/s | fp32 TFLOP/s |")
-        print("|---|---|---|---|---|---|---|")
-        for (B, N, D) in [(256, 4096, 128), (2048, 4096, 128), (32, 131072, 128), (1, 1048576, 128), (1, 131072, 8192)]:
+        print("| batch x N x D | Q | kernel | mean ms | bytes moved (GB) | GB/s | of 8 TB/s | 2*Q*elements / time (Tflop/s) |")
+        print("|---|---|---|---|---|---|---|---|")
+        for (B, N, D) in [(256, 4096, 128), (2048, 4096, 128), (32, 131072, 128), (1, 1048576, 128), (4096, 4096, 64),
+                          (512, 4096, 256), (1, 131072, 8192)]:
             E = B * N * D
             codes = torch.randint(-127, 128, (E,), dtype=torch.int8, device="cuda")
             scales = torch.rand(B * D, device="cuda") + 0.1
-            for Q in (1, 2, 4, 8):
+            for Q in (1, 2, 4, 8, 16):
                 q = torch.randn(B * Q * D, device="cuda")
                 out = torch.empty(B * Q * N, device="cuda")
                 m, _ = timeit(lambda: kvq.kvq_scores_from_codes(q, Q, codes, scales, B, N, D, out))
                 nbytes = E + 4.0 * B * Q * N + 4.0 * B * Q * D + 4.0 * B * D
-                print("| %d x %d x %d | %d | %.4f | %.4f | %.0f | %.3f | %.1f |" % (
-                    B, N, D, Q, m, nbytes / 1e9, nbytes / m / 1e6, nbytes / m / 1e6 / 8000.0, 2.0 * Q * E / m / 1e9))
+                kind = "int8 MFMA" if (Q >= 3 and D % 64 == 0 and D <= 1024) else "fp32 FMA"
+                print("| %d x %d x %d | %d | %s | %.4f | %.4f | %.0f | %.3f | %.1f |" % (
+                    B, N, D, Q, kind, m, nbytes / 1e9, nbytes / m / 1e6, nbytes / m / 1e6 / 8000.0, 2.0 * Q * E / m / 1e9))
                 sys.stdout.flush()
             del codes
             torch.cuda.empty_cache()

@@ -317,18 +317,12 @@ def scores_bound(D, fast):
     return n * 2.0 ** -24
 
 
-@pytest.mark.parametrize("shape,Q", [((1, 1024, 64), 16), ((1, 4096, 128), 1), ((6, 1000, 128), 8), ((3, 257, 128), 5),
-                                     ((1, 300, 80), 3), ((2, 100, 1024), 2), ((1, 50, 4096), 9), ((1, 33, 100), 4),
-                                     ((2, 1, 16), 1), ((1, 70, 20), 2)],
-                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else "Q%d" % v)
-def test_scores_from_codes(shape, Q):
-    batch, N, D = shape
-    rng = np.random.default_rng(N + D + Q)
-    x = make_matrix(rng, batch, N, D)
-    qs = rng.standard_normal((batch, Q, D)).astype(np.float32)
+def check_scores(x, qs, Q, offset=0):
+    """kvq_scores_from_codes against the oracle, with the bound of the kernel the shape selects."""
+    batch, N, D = x.shape
     s_ref = oracle.compute_scales(x)
     q_ref = oracle.quantize(x, s_ref)
-    g = Gpu(x)
+    g = Gpu(x, offset=offset)
     g.set_scales(s_ref)
     g.codes.copy_(torch.from_numpy(q_ref.reshape(-1)))
     qd = torch.from_numpy(qs).cuda()
@@ -336,13 +330,59 @@ def test_scores_from_codes(shape, Q):
     kvq.kvq_scores_from_codes(qd, Q, g.codes, g.scales, batch, N, D, out)
     got = out[:batch * Q * N].cpu().numpy().reshape(batch, Q, N).astype(np.float64)
     assert bool((out[batch * Q * N:] == 555.0).all())
-    fast = D % 16 == 0
+    matrix_cores = Q >= 3 and D % 64 == 0 and D <= 1024 and offset % 16 == 0
+    fast = D % 16 == 0 and offset % 16 == 0
+    worst = 0.0
     for b in range(batch):
         ref = oracle.scores_from_codes(qs[b], q_ref[b], s_ref[b])
         xh = oracle.dequantize(q_ref[b], s_ref[b]).astype(np.float64)
-        mag = np.abs(qs[b].astype(np.float64)) @ np.abs(xh).T
+        mag = np.abs(qs[b].astype(np.float64)) @ np.abs(xh).T                       # [Q, N]
+        if matrix_cores:
+            # 28-bit fixed point relative to each query's largest |q*s|; exact integer sums; one rounding
+            top = np.abs(qs[b].astype(np.float64) * s_ref[b].astype(np.float64)).max(axis=1) * (1 + 2.0 ** -23)
+            bound = 2.0 ** -27 * top[:, None] * np.abs(q_ref[b].astype(np.float64)).sum(axis=1)[None, :] \
+                + 4 * 2.0 ** -24 * mag
+        else:
+            bound = scores_bound(D, fast) * mag
+        # gradual underflow: a folded query q*s below 2^-126 carries an absolute error of up to 2^-150
+        # per channel (times |code| <= 127), and so does the final rounding of the score
+        bound = bound + (127 * D + 1) * 2.0 ** -150
         err = np.abs(got[b] - ref)
-        assert (err <= scores_bound(D, fast) * mag + 1e-300).all(), (b, float((err / (mag + 1e-300)).max()))
+        assert (err <= bound).all(), (b, float((err / bound).max()))
+        worst = max(worst, float((err / (mag + 1e-300)).max()))
+    return worst
+
+
+@pytest.mark.parametrize("shape,Q", [((1, 1024, 64), 16), ((1, 4096, 128), 1), ((6, 1000, 128), 8), ((3, 257, 128), 5),
+                                     ((1, 300, 80), 3), ((2, 100, 1024), 2), ((1, 50, 4096), 9), ((1, 33, 100), 4),
+                                     ((2, 1, 16), 1), ((1, 70, 20), 2), ((2, 700, 256), 4), ((1, 300, 2048), 3), ((1, 300, 1024), 3), ((2, 64, 192), 8),
+                                     ((4, 33, 64), 7), ((1, 5000, 128), 13), ((3, 1, 128), 8)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else "Q%d" % v)
+def test_scores_from_codes(shape, Q):
+    batch, N, D = shape
+    rng = np.random.default_rng(N + D + Q)
+    x = make_matrix(rng, batch, N, D)
+    qs = rng.standard_normal((batch, Q, D)).astype(np.float32)
+    check_scores(x, qs, Q)
+
+
+def test_scores_from_codes_matrix_core_path_corner_cases():
+    rng = np.random.default_rng(77)
+    # outlier channels (x20) and the full code range: config 2
+    x = W.generate(2)
+    worst = check_scores(x, rng.standard_normal((1, 8, 128)).astype(np.float32), 8)
+    assert worst < 2.0 ** -20
+    # queries of very different magnitude, a zero query, tiny and huge values
+    x = make_matrix(rng, 2, 200, 128)
+    qs = rng.standard_normal((2, 6, 128)).astype(np.float32)
+    qs[:, 1] *= 1e-30
+    qs[:, 2] *= 1e30
+    qs[:, 3] = 0.0
+    qs[:, 4, :64] *= 1e-6
+    check_scores(x, qs, 6)
+    check_scores((x * np.float32(1e-36)).astype(np.float32), qs[:, :5], 5)
+    # codes that are not 16-byte aligned take the vector path
+    check_scores(x, qs, 6, offset=4)
 
 
 # ------------------------------------------------------------------ fp16 / bf16 matrices
