@@ -149,11 +149,17 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options& o = options();
   const int V = (D % 4 == 0 && aligned(x, 16)) ? 4 : 1;
-  // J column groups per lane: as many as it takes for a workgroup to span whole rows, at most 8
+  // J column groups per lane: as many as it takes for a workgroup to span whole rows, at most 8 --
+  // but a wider workgroup means more row chunks for the same number of workgroups, and every chunk
+  // ends in one atomic per channel.  Keep at least about 512 rows per workgroup: measured on
+  // [16384 x 8192] J = 1 / 4 / 8 give 5.9 / 5.7 / 5.3 TB/s, on [4096 x 8192] 3.6 / 3.5 / 2.6, while
+  // from [65536 x 8192] up the wide forms win (6.3 / 6.8 / 6.8; 7.0 for J = 8 at 131072 rows).
   int J = 1;
   if (V == 4) {
     const int64_t groups = D / 4;
-    while (J < o.absmax_span && (int64_t)kBlock * J < groups) J *= 2;
+    const int64_t elements = batch * N * D;
+    const int64_t j_rows = elements / ((int64_t)dev.cus << 19);  // 512 rows x 1024 channels per unit of J
+    while (J < o.absmax_span && J * 2 <= j_rows && (int64_t)kBlock * J < groups) J *= 2;
   }
   // rows in flight: J * U 16-byte loads per lane, at most 16
   int U = o.absmax_unroll;

@@ -281,7 +281,9 @@ static kvq_status absmax16(const uint16_t* x, float* scales, int64_t batch, int6
   int J = 1;
   if (V == 8) {
     const int64_t groups = D / 8;
-    while (J < 4 && (int64_t)kBlock * J < groups) J *= 2;
+    // wide workgroups only where every one of them still gets about 512 rows (as in the fp32 reduction)
+    const int64_t j_rows = batch * N * D / ((int64_t)dev.cus << 20);
+    while (J < 4 && J * 2 <= j_rows && (int64_t)kBlock * J < groups) J *= 2;
   }
   constexpr int U1 = 8, UJ = 2;
   const int U = J == 1 ? U1 : UJ;
