@@ -4,6 +4,7 @@ Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
         python -m paper_2601_04719_amd.report --sixteen          (fp16 / bf16 matrices)
         python -m paper_2601_04719_amd.report --int4             (4-bit codes, two per byte)
         python -m paper_2601_04719_amd.report --append           (streaming append onto an int8 cache)
+        python -m paper_2601_04719_amd.report --graph            (small configurations: eager launches vs one HIP graph)
         python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
@@ -26,6 +27,7 @@ def main():
     ap.add_argument("--sixteen", action="store_true", help="fp16 / bf16 matrices: absmax, quantize, dequantize")
     ap.add_argument("--int4", action="store_true", help="4-bit codes: absmax, quantize, dequantize, max-abs error")
     ap.add_argument("--append", action="store_true", help="kvq_append: decode steps and prefill chunks")
+    ap.add_argument("--graph", action="store_true", help="launch-bound configurations: eager step vs graph replay")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
@@ -68,6 +70,38 @@ def main():
                 sys.stdout.flush()
                 del x, xh, codes
                 torch.cuda.empty_cache()
+        return
+
+    if args.graph:
+        print("| workload | step | launches | eager ms | graph replay ms |")
+        print("|---|---|---|---|---|")
+        side = torch.cuda.Stream()
+        for cfg in (1, 2):
+            c = W.CONFIGS[cfg]
+            B, N, D, E = c.batch, c.N, c.D, c.elements
+            x = torch.from_numpy(W.generate(cfg)).cuda().reshape(-1)
+            scales = torch.empty(B * D, device="cuda")
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            xh = torch.empty(E, device="cuda")
+            sumsq = torch.zeros(1, dtype=torch.float64, device="cuda")
+            maxabs = torch.zeros(1, device="cuda")
+
+            def step():
+                kvq.kvq_absmax_scales(x, scales, B, N, D)
+                kvq.kvq_quantize(x, scales, codes, B, N, D)
+                kvq.kvq_dequantize(codes, scales, xh, B, N, D)
+                kvq.kvq_roundtrip_error(x, xh, None, None, B, N, D, sumsq, maxabs)
+
+            with torch.cuda.stream(side):
+                step()
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+            te, _ = timeit(step)
+            tg, _ = timeit(graph.replay)
+            print("| %s | absmax_scales + quantize + dequantize + roundtrip_error | 7 | %.4f | %.4f |" % (c.name, te, tg))
+            sys.stdout.flush()
         return
 
     if args.append:

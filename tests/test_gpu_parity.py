@@ -811,3 +811,52 @@ def test_streaming_append_argument_errors():
         kvq.kvq_append(x, g.scales, g.scales, g.codes, 1, 0, 1, 8, 4)
     assert e.value.status == kvq.ERR_ARG
     assert bool((g.codes == 55).all())
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library enqueues only kernels (no memsets, no allocations once the per-stream workspace of
+    the error kernels exists), so a whole step can be captured once and replayed.  Each replay, with
+    eager work and synchronisation in between, must reproduce the eager results bit for bit."""
+    rng = np.random.default_rng(5)
+    batch, N, D = 3, 700, 128
+    xs = [make_matrix(rng, batch, N, D) for _ in range(3)]
+    g = Gpu(xs[0])
+    packed = torch.zeros(batch * N * D // 2, dtype=torch.uint8, device="cuda")
+    s4 = torch.zeros(batch * D, dtype=torch.float32, device="cuda")
+
+    def step():
+        kvq.kvq_absmax_scales(g.x, g.scales, batch, N, D)
+        kvq.kvq_quantize(g.x, g.scales, g.codes, batch, N, D)
+        kvq.kvq_dequantize(g.codes, g.scales, g.xh, batch, N, D)
+        kvq.kvq_roundtrip_error(g.x, g.xh, None, None, batch, N, D, g.sumsq, g.maxabs)
+        kvq.kvq_absmax_scales_int4(g.x, s4, batch, N, D)
+        kvq.kvq_quantize_int4(g.x, s4, packed, batch, N, D)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (g.scales, g.codes, g.xh, g.sumsq, g.maxabs, s4, packed)]
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                                  # creates this stream's workspace outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for x_np in xs[1:] + xs[:1]:
+        g.x.copy_(torch.from_numpy(x_np.reshape(-1)))
+        step()
+        want = snapshot()
+        for t in (g.scales, g.xh, s4):
+            t.fill_(-1.0)
+        g.codes.fill_(77)
+        packed.fill_(0x33)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b)
+    s_ref = oracle.compute_scales(xs[0])
+    assert_bits_equal(g.scales.cpu().numpy().reshape(batch, D), s_ref, "scales after the last replay")
+    assert_bits_equal(g.codes.cpu().numpy().reshape(batch, N, D), oracle.quantize(xs[0], s_ref), "codes after replay")
