@@ -46,6 +46,15 @@ def lib():
             L.kvq_oracle_compute_scales_q.restype = None
             L.kvq_oracle_quantize_q.argtypes = [_fp, _fp, _bp, _i64, _i64, _i64, ctypes.c_int]
             L.kvq_oracle_quantize_q.restype = None
+            _u8 = ctypes.POINTER(ctypes.c_uint8)
+            L.kvq_oracle_fp8_encode.argtypes = [_fp, _u8, _i64]
+            L.kvq_oracle_fp8_encode.restype = None
+            L.kvq_oracle_fp8_decode.argtypes = [_u8, _fp, _i64]
+            L.kvq_oracle_fp8_decode.restype = None
+            L.kvq_oracle_quantize_fp8.argtypes = [_fp, _fp, _u8, _i64, _i64, _i64]
+            L.kvq_oracle_quantize_fp8.restype = None
+            L.kvq_oracle_dequantize_fp8.argtypes = [_u8, _fp, _fp, _i64, _i64, _i64]
+            L.kvq_oracle_dequantize_fp8.restype = None
             _lib = L
     return _lib
 
@@ -259,3 +268,53 @@ def append(codes, scales, n_old, x_new):
         out[:, :n_old] = np.where(grew[:, None, :], again, cached)
     out[:, n_old:n_old + m] = quantize(x_new, s_new)
     return out, s_new, s_old.copy()
+
+
+# ---------------------------------------------------------------------------------------------
+# FP8 codes (Future Work, "GPU-specific numeric formats such as FP8"): OCP E4M3 instead of int8
+# ---------------------------------------------------------------------------------------------
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+
+
+def fp8_encode(y):
+    """float32 -> E4M3 bit patterns (uint8): round to nearest even, saturate at +-448."""
+    y = _f32(y)
+    out = np.empty(y.shape, dtype=np.uint8)
+    lib().kvq_oracle_fp8_encode(_ptr(y, _fp), _ptr(out, _u8p), y.size)
+    return out
+
+
+def fp8_decode(codes):
+    """E4M3 bit patterns (uint8, no NaN patterns) -> float32 (exact)."""
+    codes = np.ascontiguousarray(codes)
+    if codes.dtype != np.uint8:
+        raise TypeError("expected uint8")
+    out = np.empty(codes.shape, dtype=np.float32)
+    lib().kvq_oracle_fp8_decode(_ptr(codes, _u8p), _ptr(out, _fp), codes.size)
+    return out
+
+
+def quantize_fp8(x, scales):
+    """codes = E4M3(x / scale) as uint8; 0 where scale == 0."""
+    x = _f32(x)
+    scales = _f32(scales)
+    b, n, d = _shape3(x)
+    if scales.size != b * d:
+        raise ValueError("scales must hold batch*D values")
+    out = np.empty(x.shape, dtype=np.uint8)
+    lib().kvq_oracle_quantize_fp8(_ptr(x, _fp), _ptr(scales, _fp), _ptr(out, _u8p), b, n, d)
+    return out
+
+
+def dequantize_fp8(codes, scales):
+    """x_hat = value(code) * scale (fp32)."""
+    codes = np.ascontiguousarray(codes)
+    if codes.dtype != np.uint8:
+        raise TypeError("expected uint8 codes")
+    scales = _f32(scales)
+    b, n, d = _shape3(codes)
+    if scales.size != b * d:
+        raise ValueError("scales must hold batch*D values")
+    out = np.empty(codes.shape, dtype=np.float32)
+    lib().kvq_oracle_dequantize_fp8(_ptr(codes, _u8p), _ptr(scales, _fp), _ptr(out, _fp), b, n, d)
+    return out

@@ -212,3 +212,71 @@ void kvq_oracle_quantize_q(const float *x, const float *scales, int8_t *codes,
         }
     }
 }
+
+/* FP8 codes (Future Work: "GPU-specific numeric formats such as FP8"): the per-channel scheme with
+ * the 8-bit code an OCP E4M3 floating-point number (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits; largest finite value 448; the all-ones pattern is NaN and is never produced) instead of an
+ * integer:  scale = absmax / 448,  code = E4M3(x / scale) rounded to nearest even and saturated at
+ * +-448,  x_hat = value(code) * scale.  A zero scale gives code 0. */
+static uint8_t e4m3_from_float(float y)
+{
+    uint8_t sign = signbit(y) ? 0x80 : 0x00;
+    float a = fabsf(y);
+    if (!(a < 448.0f))
+        return sign | 0x7E;                      /* 448 and everything above saturates */
+    if (a < 0.015625f) {                         /* below 2^-6: multiples of 2^-9 */
+        int q = (int)rintf(a * 512.0f);          /* exact scaling; 8 is 2^-6, the smallest normal */
+        return sign | (uint8_t)q;
+    }
+    int e;
+    float m = frexpf(a, &e);                     /* a = m * 2^e, m in [0.5, 1) */
+    int idx = (int)rintf((m * 2.0f - 1.0f) * 8.0f); /* exact operand; ties to even */
+    e -= 1;                                      /* a = (1 + f) * 2^e */
+    if (idx == 8) {
+        idx = 0;
+        e += 1;
+    }
+    return sign | (uint8_t)(((e + 7) << 3) | idx);
+}
+
+static float e4m3_to_float(uint8_t c)
+{
+    int E = (c >> 3) & 15, M = c & 7;
+    float v = E ? ldexpf(1.0f + (float)M / 8.0f, E - 7) : ldexpf((float)M, -9);
+    return (c & 0x80) ? -v : v;
+}
+
+void kvq_oracle_fp8_encode(const float *y, uint8_t *codes, int64_t count)
+{
+    for (int64_t i = 0; i < count; i++)
+        codes[i] = e4m3_from_float(y[i]);
+}
+
+void kvq_oracle_fp8_decode(const uint8_t *codes, float *y, int64_t count)
+{
+    for (int64_t i = 0; i < count; i++)
+        y[i] = e4m3_to_float(codes[i]);
+}
+
+void kvq_oracle_quantize_fp8(const float *x, const float *scales, uint8_t *codes,
+                             int64_t batch, int64_t N, int64_t D)
+{
+    for (int64_t b = 0; b < batch; b++)
+        for (int64_t t = 0; t < N; t++)
+            for (int64_t d = 0; d < D; d++) {
+                size_t i = ((size_t)b * (size_t)N + (size_t)t) * (size_t)D + (size_t)d;
+                float s = scales[(size_t)b * (size_t)D + (size_t)d];
+                codes[i] = s != 0.0f ? e4m3_from_float(x[i] / s) : 0;
+            }
+}
+
+void kvq_oracle_dequantize_fp8(const uint8_t *codes, const float *scales, float *x_hat,
+                               int64_t batch, int64_t N, int64_t D)
+{
+    for (int64_t b = 0; b < batch; b++)
+        for (int64_t t = 0; t < N; t++)
+            for (int64_t d = 0; d < D; d++) {
+                size_t i = ((size_t)b * (size_t)N + (size_t)t) * (size_t)D + (size_t)d;
+                x_hat[i] = e4m3_to_float(codes[i]) * scales[(size_t)b * (size_t)D + (size_t)d];
+            }
+}

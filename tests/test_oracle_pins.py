@@ -529,3 +529,76 @@ def test_append_from_empty_equals_batch_and_scales_track_the_running_absmax():
     bound = (grow_events + 1)[:, None, :] * s.astype(np.float64)[:, None, :] / 2 * (1 + 2.0 ** -15)
     assert (err <= bound).all()
     assert (np.abs(cache[:, :N].astype(np.int32)) <= 127).all()
+
+
+# --------------------------------------------------------------------------
+# FP8 (E4M3) codes
+# --------------------------------------------------------------------------
+def e4m3_value(c):
+    """The format's definition: sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent 0 is subnormal."""
+    E, M = (c >> 3) & 15, c & 7
+    v = Fraction(M, 8) * Fraction(1, 64) if E == 0 else (1 + Fraction(M, 8)) * Fraction(2) ** (E - 7)
+    return -v if c & 0x80 else v
+
+
+FP8_FINITE = [c for c in range(256) if c & 0x7F != 0x7F]
+
+
+def nearest_e4m3(v, negative=None):
+    """Brute force over the 127 non-negative values: nearest, ties to the even mantissa, saturating.
+    The sign bit follows the sign of the input (negative=True marks -0.0)."""
+    mag = abs(v)
+    grid = [(e4m3_value(c), c) for c in range(0x7F)]
+    best = min(grid, key=lambda gc: (abs(gc[0] - mag), gc[1] & 1))
+    if negative is None:
+        negative = v < 0
+    return best[1] | (0x80 if negative else 0)
+
+
+def test_fp8_decode_is_the_format_definition_and_encode_inverts_it():
+    codes = np.array(FP8_FINITE, dtype=np.uint8)
+    vals = oracle.fp8_decode(codes)
+    for c, v in zip(FP8_FINITE, vals):
+        assert Fraction(float(v)) == e4m3_value(c)
+    assert float(vals.max()) == 448.0 and e4m3_value(0x01) == Fraction(1, 512) and e4m3_value(0x08) == Fraction(1, 64)
+    assert np.array_equal(oracle.fp8_encode(vals), codes)            # every value is its own code (+-0 too)
+
+
+def test_fp8_encode_rounds_to_nearest_even_and_saturates():
+    pos = sorted(e4m3_value(c) for c in range(0x7F))
+    cases = []
+    for lo, hi in zip(pos[:-1], pos[1:]):
+        mid = (lo + hi) / 2
+        cases += [mid, mid * (1 + Fraction(1, 2 ** 20)), mid * (1 - Fraction(1, 2 ** 20)), lo, hi]
+    cases += [Fraction(448), Fraction(449), Fraction(463), Fraction(464), Fraction(480), Fraction(10 ** 30),
+              Fraction(1, 1024), Fraction(1, 1025), Fraction(3, 2048), Fraction(1, 10 ** 30), Fraction(0)]
+    y = np.array([float(v) for v in cases] + [-float(v) for v in cases], dtype=np.float32)
+    got = oracle.fp8_encode(y)
+    for v, c in zip(y, got):
+        assert int(c) == nearest_e4m3(Fraction(float(v)), bool(np.signbit(v))), (float(v), hex(int(c)))
+    assert oracle.fp8_encode(np.array([np.inf, -np.inf], dtype=np.float32)).tolist() == [0x7E, 0xFE]
+    # hand-picked: 0.0029296875 = 1.5 * 2^-9 is a tie between codes 1 and 2 -> 2; 17 is a tie between 16 and 18 -> 16
+    assert oracle.fp8_encode(np.array([1.5 / 512, 17.0, 19.0, 0.3], dtype=np.float32)).tolist() == [0x02, 0x58, 0x5A, 0x2A]
+
+
+def test_fp8_quantize_against_exact_rationals_and_error_bound():
+    rng = np.random.default_rng(43)
+    x = (rng.standard_normal((60, 5)) * np.exp(rng.uniform(-2, 2, 5))).astype(np.float32)
+    x[:, 4] = 0.0
+    absmax = np.abs(x).max(axis=0)
+    s = (absmax / np.float32(448.0)).astype(np.float32)
+    q = oracle.quantize_fp8(x, s)
+    xh = oracle.dequantize_fp8(q, s)
+    for d in range(5):
+        for t in range(60):
+            if s[d] == 0:
+                assert q[t, d] == 0
+                continue
+            y32 = fl32(Fraction(float(x[t, d])) / Fraction(float(s[d])))
+            assert int(q[t, d]) == nearest_e4m3(y32, bool(np.signbit(x[t, d])))
+            assert Fraction(float(xh[t, d])) == fl32(e4m3_value(int(q[t, d])) * Fraction(float(s[d])))
+    assert (q[:, :4] & 0x7F).max() == 0x7E                     # the absmax entry lands on 448
+    # relative error of a normal code <= 2^-4 (half of a 3-bit mantissa step), absolute floor 2^-10 * s
+    err = np.abs(x.astype(np.float64) - xh)
+    bound = np.maximum(np.abs(x).astype(np.float64) * 2.0 ** -4, s.astype(np.float64)[None, :] * 2.0 ** -10)
+    assert (err <= bound * (1 + 1e-6)).all()
