@@ -119,6 +119,28 @@ kvq_status kvq_dequantize_int4(const uint8_t *packed, const float *scales, float
                                int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
 
 /*
+ * The same method with FP8 codes -- Future Work ("GPU-specific numeric formats such as
+ * FP8").  The 8-bit code is an OCP E4M3 number (1 sign, 4 exponent bits with bias 7, 3
+ * mantissa bits, subnormals, largest finite value 448; the NaN patterns 0x7F / 0xFF are
+ * never produced) instead of an integer:
+ *   scales[b,d]  = max_t |x[b,t,d]| / 448
+ *   code[b,t,d]  = E4M3(x[b,t,d] / scales[b,d]): the fp32 quotient (same divide as the int8
+ *                  call) rounded to the nearest E4M3 value, ties to the even mantissa,
+ *                  saturated at +-448; the sign of the quotient is kept (so -0 exists);
+ *                  0x00 where the scale is 0
+ *   x_hat[b,t,d] = value(code) * scales[b,d]   (value() exact in fp32, one multiply)
+ * Relative error of a reconstructed value is at most 2^-4 (half a mantissa step) down to
+ * |x| = scale * 2^-6, against the absolute bound scale/2 of the integer codes.
+ *   x / x_hat [batch,N,D] fp32, scales [batch,D] fp32, codes [batch,N,D] uint8: device
+ */
+kvq_status kvq_absmax_scales_fp8(const float *x, float *scales,
+                                 int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+kvq_status kvq_quantize_fp8(const float *x, const float *scales, uint8_t *codes,
+                            int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+kvq_status kvq_dequantize_fp8(const uint8_t *codes, const float *scales, float *x_hat,
+                              int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
  * Streaming append -- Limitations, "Dynamic quantization" (scales that adapt during
  * inference) and Future Work (streaming workloads), with the operations of Eq. (scale),
  * Eq. (quant_op) and Eq. (dequant_op).  A cache of n_old tokens exists only as int8

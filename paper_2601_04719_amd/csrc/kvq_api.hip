@@ -199,6 +199,27 @@ kvq_status kvq_dequantize_int4(const uint8_t* packed, const float* scales, float
   return launch_dequantize_int4(packed, scales, x_hat, batch, N, D, stream);
 }
 
+kvq_status kvq_absmax_scales_fp8(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                 kvq_stream_t stream) {
+  if (!x || !scales) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_absmax_scales(x, scales, batch, N, D, stream, 448.0f);
+}
+
+kvq_status kvq_quantize_fp8(const float* x, const float* scales, uint8_t* codes, int64_t batch, int64_t N,
+                            int64_t D, kvq_stream_t stream) {
+  if (!x || !scales || !codes) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_quantize_fp8(x, scales, codes, batch, N, D, stream);
+}
+
+kvq_status kvq_dequantize_fp8(const uint8_t* codes, const float* scales, float* x_hat, int64_t batch, int64_t N,
+                              int64_t D, kvq_stream_t stream) {
+  if (!codes || !scales || !x_hat) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  return launch_dequantize_fp8(codes, scales, x_hat, batch, N, D, stream);
+}
+
 kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
                       int64_t n_old, int64_t m, int64_t capacity, int64_t D, kvq_stream_t stream) {
   if (!x_new || !scales || !scales_prev || !codes) return KVQ_ERR_NULL;

@@ -94,6 +94,11 @@ kvq_status launch_quantize_int4(const float* x, const float* scales, uint8_t* pa
                                 int64_t D, hipStream_t stream);
 kvq_status launch_dequantize_int4(const uint8_t* packed, const float* scales, float* x_hat, int64_t batch,
                                   int64_t N, int64_t D, hipStream_t stream);
+// FP8 (OCP E4M3) codes, one byte per element; scales = absmax / 448.
+kvq_status launch_quantize_fp8(const float* x, const float* scales, uint8_t* codes, int64_t batch, int64_t N,
+                               int64_t D, hipStream_t stream);
+kvq_status launch_dequantize_fp8(const uint8_t* codes, const float* scales, float* x_hat, int64_t batch, int64_t N,
+                                 int64_t D, hipStream_t stream);
 kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
                            int64_t D, hipStream_t stream);
 // The same with separate slab pitches (in elements, multiples of D) for x and codes.

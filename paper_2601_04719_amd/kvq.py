@@ -24,6 +24,7 @@ EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
     "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append",
+    "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
 )
@@ -62,6 +63,11 @@ def lib():
         L.kvq_quantize_int4.argtypes = [p, p, p, i64, i64, i64, p]
         L.kvq_dequantize_int4.argtypes = [p, p, p, i64, i64, i64, p]
         for name in ("kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4"):
+            getattr(L, name).restype = i32
+        L.kvq_absmax_scales_fp8.argtypes = [p, p, i64, i64, i64, p]
+        L.kvq_quantize_fp8.argtypes = [p, p, p, i64, i64, i64, p]
+        L.kvq_dequantize_fp8.argtypes = [p, p, p, i64, i64, i64, p]
+        for name in ("kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8"):
             getattr(L, name).restype = i32
         L.kvq_append.argtypes = [p, p, p, p, i64, i64, i64, i64, i64, p]
         L.kvq_append.restype = i32
@@ -162,6 +168,21 @@ def kvq_quantize_int4(x, scales, packed, batch, N, D, stream=None):
 def kvq_dequantize_int4(packed, scales, x_hat, batch, N, D, stream=None):
     _check(lib().kvq_dequantize_int4(_addr(packed), _addr(scales), _addr(x_hat), batch, N, D, _stream(stream)),
            "kvq_dequantize_int4")
+
+
+def kvq_absmax_scales_fp8(x, scales, batch, N, D, stream=None):
+    _check(lib().kvq_absmax_scales_fp8(_addr(x), _addr(scales), batch, N, D, _stream(stream)),
+           "kvq_absmax_scales_fp8")
+
+
+def kvq_quantize_fp8(x, scales, codes, batch, N, D, stream=None):
+    _check(lib().kvq_quantize_fp8(_addr(x), _addr(scales), _addr(codes), batch, N, D, _stream(stream)),
+           "kvq_quantize_fp8")
+
+
+def kvq_dequantize_fp8(codes, scales, x_hat, batch, N, D, stream=None):
+    _check(lib().kvq_dequantize_fp8(_addr(codes), _addr(scales), _addr(x_hat), batch, N, D, _stream(stream)),
+           "kvq_dequantize_fp8")
 
 
 def kvq_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):

@@ -5,6 +5,7 @@ Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
         python -m paper_2601_04719_amd.report --int4             (4-bit codes, two per byte)
         python -m paper_2601_04719_amd.report --append           (streaming append onto an int8 cache)
         python -m paper_2601_04719_amd.report --graph            (small configurations: eager launches vs one HIP graph)
+        python -m paper_2601_04719_amd.report --fp8              (FP8 E4M3 codes)
         python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
@@ -28,6 +29,7 @@ def main():
     ap.add_argument("--int4", action="store_true", help="4-bit codes: absmax, quantize, dequantize, max-abs error")
     ap.add_argument("--append", action="store_true", help="kvq_append: decode steps and prefill chunks")
     ap.add_argument("--graph", action="store_true", help="launch-bound configurations: eager step vs graph replay")
+    ap.add_argument("--fp8", action="store_true", help="FP8 (E4M3) codes: absmax, quantize, dequantize, errors")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
@@ -138,6 +140,37 @@ def main():
                                                                            mean - tc, mn - tc))
                 sys.stdout.flush()
             del codes
+            torch.cuda.empty_cache()
+        return
+
+    if args.fp8:
+        print("| workload | absmax/448 ms (GB/s, of 8 TB/s) | quantize ms (GB/s, of 8 TB/s) | dequantize ms (GB/s, of 8 TB/s) "
+              "| L2 error fp8 | L2 error int8 | max-abs error fp8 | max-abs error int8 |")
+        print("|---|---|---|---|---|---|---|---|")
+        sumsq = torch.zeros(1, dtype=torch.float64, device="cuda")
+        maxabs = torch.zeros(1, dtype=torch.float32, device="cuda")
+        for cfg in [int(c) for c in args.configs.split(",")]:
+            c = W.CONFIGS[cfg]
+            B, N, D, E = c.batch, c.N, c.D, c.elements
+            x = torch.from_numpy(W.generate(cfg)).cuda().reshape(-1)
+            scales = torch.empty(B * D, device="cuda")
+            codes = torch.empty(E, dtype=torch.uint8, device="cuda")
+            xh = torch.empty(E, device="cuda")
+            ta, _ = timeit(lambda: kvq.kvq_absmax_scales_fp8(x, scales, B, N, D))
+            tq, _ = timeit(lambda: kvq.kvq_quantize_fp8(x, scales, codes, B, N, D))
+            td, _ = timeit(lambda: kvq.kvq_dequantize_fp8(codes, scales, xh, B, N, D))
+            kvq.kvq_roundtrip_error(x, xh, None, None, B, N, D, sumsq, maxabs)
+            l8, m8 = float(sumsq.item()) ** 0.5, float(maxabs.item())
+            icodes = codes.view(torch.int8)
+            kvq.kvq_absmax_scales(x, scales, B, N, D)
+            kvq.kvq_quantize(x, scales, icodes, B, N, D)
+            kvq.kvq_roundtrip_error(x, None, icodes, scales, B, N, D, sumsq, maxabs)
+            li, mi = float(sumsq.item()) ** 0.5, float(maxabs.item())
+            cell = lambda t, bpe: "%.4f (%.0f, %.3f)" % (t, bpe * E / t / 1e6, bpe * E / t / 1e6 / 8000.0)
+            print("| %s | %s | %s | %s | %.4g | %.4g | %.4g | %.4g |" % (c.name, cell(ta, 4.0), cell(tq, 5.0), cell(td, 5.0),
+                                                                        l8, li, m8, mi))
+            sys.stdout.flush()
+            del x, xh, codes
             torch.cuda.empty_cache()
         return
 

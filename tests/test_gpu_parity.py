@@ -860,3 +860,94 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     s_ref = oracle.compute_scales(xs[0])
     assert_bits_equal(g.scales.cpu().numpy().reshape(batch, D), s_ref, "scales after the last replay")
     assert_bits_equal(g.codes.cpu().numpy().reshape(batch, N, D), oracle.quantize(xs[0], s_ref), "codes after replay")
+
+
+# ------------------------------------------------------------------ FP8 (E4M3) codes
+def fp8_round_trip(x, offset=0, given_scales=None):
+    """kvq_*_fp8 against the oracle: scales (absmax / 448), E4M3 codes and x_hat bit-exact."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.ndim == 2:
+        x = x[None]
+    batch, N, D = x.shape
+    n = x.size
+    dx = torch.empty(n + 64, dtype=torch.float32, device="cuda")
+    xs = dx[offset:offset + n]
+    xs.copy_(torch.from_numpy(x.reshape(-1)))
+    ds = torch.full((batch * D + 64,), -5.0, dtype=torch.float32, device="cuda")
+    ss = ds[offset:offset + batch * D]
+    dc = torch.full((n + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    cs = dc[offset:offset + n]
+    dh = torch.full((n + 64,), 777.0, dtype=torch.float32, device="cuda")
+    hs = dh[offset:offset + n]
+    if given_scales is None:
+        kvq.kvq_absmax_scales_fp8(xs, ss, batch, N, D)
+        s_ref = oracle.compute_scales_q(x, 448).reshape(batch, D)
+        assert_bits_equal(ss.cpu().numpy().reshape(batch, D), s_ref, "fp8 scales")
+    else:
+        s_ref = np.ascontiguousarray(given_scales, dtype=np.float32).reshape(batch, D)
+        ss.copy_(torch.from_numpy(s_ref.reshape(-1)))
+    kvq.kvq_quantize_fp8(xs, ss, cs, batch, N, D)
+    q_ref = oracle.quantize_fp8(x, s_ref)
+    assert_bits_equal(cs.cpu().numpy().reshape(x.shape), q_ref, "E4M3 codes")
+    kvq.kvq_dequantize_fp8(cs, ss, hs, batch, N, D)
+    assert_bits_equal(hs.cpu().numpy().reshape(x.shape), oracle.dequantize_fp8(q_ref, s_ref), "fp8 x_hat")
+    torch.cuda.synchronize()
+    assert bool((dc[:offset] == 0x5A).all() and (dc[offset + n:] == 0x5A).all())
+    assert bool((dh[:offset] == 777.0).all() and (dh[offset + n:] == 777.0).all())
+    assert bool((ds[:offset] == -5.0).all() and (ds[offset + batch * D:] == -5.0).all())
+    return q_ref
+
+
+@pytest.mark.parametrize("shape", SHAPES + [(1, 1024, 64), (8, 515, 128)], ids=lambda s: "x".join(map(str, s)))
+def test_fp8_ragged_shapes(shape):
+    rng = np.random.default_rng(hash(shape) % (1 << 31))
+    q = fp8_round_trip(make_matrix(rng, *shape))
+    assert ((q & 0x7F) != 0x7F).all()                       # no NaN patterns
+
+
+@pytest.mark.parametrize("offset", [1, 2, 3, 4, 8])
+def test_fp8_unaligned_base_pointers(offset):
+    rng = np.random.default_rng(offset)
+    fp8_round_trip(make_matrix(rng, 2, 70, 64), offset=offset)
+
+
+def test_fp8_encode_on_a_dense_grid_of_quotients_and_decode_of_every_code():
+    """Scale 1 makes the quotient the input itself: every fp32 pattern with 12 low zero bits in the
+    range of interest, the neighbourhoods of all rounding boundaries, huge, tiny, subnormal and zero."""
+    pats = (np.arange(1 << 20, dtype=np.uint64) << np.uint64(12)).astype(np.uint32)
+    y = pats.view(np.float32)
+    y = y[np.isfinite(y)]
+    vals = oracle.fp8_decode(np.arange(0x7F, dtype=np.uint8)).astype(np.float64)
+    mids = ((vals[:-1] + vals[1:]) / 2).astype(np.float32)
+    near = np.concatenate([(mids.view(np.uint32).astype(np.int64) + k).astype(np.uint32) for k in range(-3, 4)]).view(np.float32)
+    extra = np.array([448.0, 464.0, 463.99, 480.0, 3e38, 1e-45, 2.0 ** -10, 2.0 ** -9, 2.0 ** -126, 0.0],
+                     dtype=np.float32)
+    y = np.concatenate([y, near, -near, vals[1:].astype(np.float32), extra, -extra])
+    D = 64
+    y = y[:y.size // D * D].reshape(-1, D)
+    fp8_round_trip(y, given_scales=np.ones(D, dtype=np.float32))
+    # every finite code through dequantize, with assorted scales (zero, negative, tiny, huge)
+    codes = np.array([c for c in range(256) if c & 0x7F != 0x7F] * 16 + [0] * 32, dtype=np.uint8)
+    codes = codes[:codes.size // D * D].reshape(-1, D)
+    s = np.exp(np.random.default_rng(2).uniform(-20, 20, D)).astype(np.float32)
+    s[0], s[1], s[2], s[3] = 0.0, -0.25, 2.0 ** -140, 2.0 ** 118
+    dcodes = torch.from_numpy(codes).cuda()
+    dsc = torch.from_numpy(s).cuda()
+    out = torch.empty(codes.shape, dtype=torch.float32, device="cuda")
+    kvq.kvq_dequantize_fp8(dcodes, dsc, out, 1, codes.shape[0], D)
+    assert_bits_equal(out.cpu().numpy(), oracle.dequantize_fp8(codes, s), "fp8 decode of every code")
+
+
+def test_fp8_special_scales_and_configs():
+    rng = np.random.default_rng(29)
+    N, D = 2048, 64
+    s = np.exp(rng.uniform(-3, 3, D)).astype(np.float32)
+    s[0], s[1], s[2], s[3], s[4], s[5] = 2.0 ** -140, 2.0 ** 120, 1e-3, 3.0, 0.0, -0.25
+    x = (rng.standard_normal((N, D)) * np.clip(s, -1e30, 1e30) * 100).astype(np.float32)
+    x[:, 0] = (rng.integers(-200, 200, N) * 2.0 ** -141).astype(np.float32)
+    x[:, 1] = (rng.standard_normal(N) * 2.0 ** 125).astype(np.float32)
+    x[::7, 4] = -0.0
+    fp8_round_trip(x, given_scales=s)
+    q = fp8_round_trip(W.generate(2)[0])
+    assert len(np.unique(q)) > 200
+    fp8_round_trip(W.generate(3, slabs=(0, 24)))
