@@ -13,10 +13,10 @@ namespace kvq {
 constexpr int kAbX = 64, kAbY = 4;
 
 __device__ __forceinline__ int8_t ab_code(float x, float s) {
-  const float d = s == 0.0f ? __builtin_inff() : s;
+  const float d = divisor_of(s);
   float y = x / d;
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
-  return (int8_t)(__float_as_uint(y + 12582912.0f) & 0xffu);
+  return (int8_t)(__float_as_uint(y + kRoundMagic) & 0xffu);
 }
 
 // "naive": one lane per element; every lane fetches its own scale.

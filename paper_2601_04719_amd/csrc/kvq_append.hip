@@ -30,16 +30,13 @@ namespace kvq {
 
 namespace {
 
-constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23
 constexpr int kSmallM = 16;            // up to this many new tokens the one-kernel path is used
-
-__device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
 
 // int8 code of v for divisor s, in the low byte of the result
 __device__ __forceinline__ uint32_t code_bits(float v, float s) {
   float y = v / s;
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
-  return __float_as_uint(y + kMagic) & 0xffu;
+  return __float_as_uint(y + kRoundMagic) & 0xffu;
 }
 
 __device__ __forceinline__ float merged(float old, float cand) { return cand > old ? cand : old; }

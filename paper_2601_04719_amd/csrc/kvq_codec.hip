@@ -20,25 +20,18 @@
 //    is re-read.
 //
 // Rounding is done without a convert instruction: after the clamp to
-// [-127,127], adding 1.5*2^23 rounds to the nearest integer with ties to even
-// (the sum lies in [2^23,2^24) where the spacing is 1 and 1.5*2^23 is even) and
-// leaves the two's-complement code in the low byte of the sum's bit pattern.
+// [-127,127], adding kRoundMagic leaves the int8 code in the low byte of the sum.
 #include <type_traits>
 
 #include "kvq_internal.h"
 
 namespace kvq {
 
-constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23
-
-// Divisor for a channel: its scale, or +inf for a zero scale (x / inf = +-0 -> code 0).
-__device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
-
 // Returns the float whose low byte is the int8 code of x for divisor s.
 __device__ __forceinline__ float code_as_float(float x, float s) {
   float y = x / s;  // correctly rounded IEEE divide (the full v_div_scale/fmas/fixup sequence)
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
-  return y + kMagic;
+  return y + kRoundMagic;
 }
 
 // low bytes of four words -> one word (a in byte 0 ... d in byte 3)

@@ -27,8 +27,6 @@ namespace kvq {
 
 namespace {
 
-__device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
-
 // E4M3 bit pattern (low byte) of x / s; `keep` is 0 for a zero scale (code 0) and 0xff otherwise.
 __device__ __forceinline__ uint32_t e4m3_of(float x, float s, uint32_t keep) {
   const float y = x / s;  // correctly rounded IEEE divide

@@ -15,7 +15,6 @@ namespace kvq {
 constexpr int kFusedBlock = 1024;
 constexpr int kFusedMaxRows = 16;  // rows per lane
 
-constexpr float kFusedMagic = 12582912.0f;  // 1.5 * 2^23: see the quantize kernel
 
 template <int R>
 __global__ __launch_bounds__(kFusedBlock) void fused_slab_kernel(const float* __restrict__ x,
@@ -60,7 +59,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_slab_kernel(const float* __
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     sc[i] = red[i][tx] / 127.0f;                           // the one IEEE divide per channel
-    div[i] = sc[i] == 0.0f ? __builtin_inff() : sc[i];     // zero scale: x / inf = 0 -> code 0
+    div[i] = divisor_of(sc[i]);
   }
   if (active && ty == 0) *reinterpret_cast<f32x4*>(scales + slab * D + (int64_t)tx * 4) = sc;
 
@@ -73,7 +72,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_slab_kernel(const float* __
       for (int i = 0; i < 4; i++) {
         float y = v[u][i] / div[i];
         y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
-        w |= (__float_as_uint(y + kFusedMagic) & 0xffu) << (8 * i);
+        w |= (__float_as_uint(y + kRoundMagic) & 0xffu) << (8 * i);
       }
       __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(cs + row * D));
     }

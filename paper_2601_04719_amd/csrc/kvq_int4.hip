@@ -17,15 +17,11 @@ namespace kvq {
 
 namespace {
 
-constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to nearest even, code in the low bits
-
-__device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
-
 // bit pattern whose low 4 bits are the two's-complement 4-bit code of x for divisor s
 __device__ __forceinline__ uint32_t nibble_bits(float x, float s) {
   float y = x / s;  // correctly rounded IEEE divide
   y = __builtin_amdgcn_fmed3f(y, -7.0f, 7.0f);
-  return __float_as_uint(y + kMagic);
+  return __float_as_uint(y + kRoundMagic);
 }
 
 // signed 4-bit field i of w -> float (exact) times the channel's scale (one rounding)

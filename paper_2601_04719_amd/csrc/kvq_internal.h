@@ -153,6 +153,15 @@ __device__ __forceinline__ void st(T* p, T v) {
   else *p = v;
 }
 
+// Rounding without a convert instruction: once a value is clamped to a range inside [-2^22, 2^22],
+// adding 1.5 * 2^23 rounds it to the nearest integer with ties to even (the sum lies in [2^23, 2^24)
+// where the spacing is 1, and 1.5 * 2^23 is even) and leaves the two's-complement integer in the low
+// bits of the sum's bit pattern.
+constexpr float kRoundMagic = 12582912.0f;
+
+// Divisor for a channel: its scale, or +inf for a zero scale (x / inf = +-0 -> code 0).
+__device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
+
 // Decomposition of a work-item index into (slab, row chunk, column tile).
 struct Item {
   int64_t slab;

@@ -55,14 +55,13 @@ __device__ __forceinline__ void widen8(const u16x8& raw, float (&out)[8]) {
   for (int i = 0; i < 8; i++) out[i] = widen<T>(raw[i]);
 }
 
-constexpr float kMagic16 = 12582912.0f;  // 1.5 * 2^23, see the fp32 quantize kernel
 
 // Plain IEEE divide: a reciprocal-multiply shortcut with an exact fallback near ties was measured on
 // this kernel too (3 bytes of traffic per element) and was slower (4.1-4.9 TB/s against 5.2).
 __device__ __forceinline__ uint32_t code_byte(float x, float div) {
   float y = x / div;
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
-  return __float_as_uint(y + kMagic16) & 0xffu;
+  return __float_as_uint(y + kRoundMagic) & 0xffu;
 }
 
 // ---- absmax --------------------------------------------------------------------------------
@@ -170,11 +169,11 @@ __global__ __launch_bounds__(kMaxBlock) void quantize16_kernel(const uint16_t* _
     for (int w = 0; w < 2; w++) {
       const f32x4 sv = *(reinterpret_cast<const f32x4*>(scales + it.slab * D + col) + w);
 #pragma unroll
-      for (int i = 0; i < 4; i++) div[4 * w + i] = sv[i] == 0.0f ? __builtin_inff() : sv[i];
+      for (int i = 0; i < 4; i++) div[4 * w + i] = divisor_of(sv[i]);
     }
   } else {
     const float s = scales[it.slab * D + col];
-    div[0] = s == 0.0f ? __builtin_inff() : s;
+    div[0] = divisor_of(s);
   }
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
