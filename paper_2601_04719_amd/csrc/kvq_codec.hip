@@ -249,26 +249,9 @@ static kvq_status dispatch_vu(int V, int U, F&& f) {
 static kvq_status codec_tiling(int64_t batch, int64_t N, int64_t D, const void* fp32_ptr, const void* int8_ptr,
                                const float* scales, int default_unroll, int default_block, int* U_out,
                                Tiling* t_out) {
-  const DeviceInfo dev = current_device();
-  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
-  const Options o = options();
-  int V = pick_width(D, fp32_ptr, int8_ptr, o.codec_width);
+  int V = pick_width(D, fp32_ptr, int8_ptr, options().codec_width);
   if (V > 1 && !aligned(scales, 16)) V = 1;
-  int U = o.codec_unroll > 0 ? o.codec_unroll : default_unroll;
-  if (V == 1) U = 1;
-  else if (V > 4 && U > 4) U = 4;
-  int passes = o.passes_per_block;
-  const int block = o.block_threads > 0 ? o.block_threads : default_block;
-  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
-  // one-shot workgroups by default; fall back to longer walks only when the grid would not be indexable
-  while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
-    passes *= 2;
-    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
-  }
-  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  *U_out = U;
-  *t_out = t;
-  return KVQ_OK;
+  return stream_tiling(batch, N, D, V, V > 1, default_unroll, default_block, U_out, t_out);
 }
 
 kvq_status launch_quantize(const float* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,

@@ -136,23 +136,8 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_fp8_kernel(const uint8_t
 
 kvq_status fp8_tiling(int64_t batch, int64_t N, int64_t D, const void* fp32_ptr, const void* codes,
                       const float* scales, int default_unroll, int default_block, int* U_out, Tiling* t_out) {
-  const DeviceInfo dev = current_device();
-  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
-  const Options o = options();
-  const int V = (D % 4 == 0 && aligned(fp32_ptr, 16) && aligned(codes, 4) && aligned(scales, 16)) ? 4 : 1;
-  int U = o.codec_unroll > 0 ? o.codec_unroll : default_unroll;
-  if (V == 1) U = 1;
-  int passes = o.passes_per_block;
-  const int block = o.block_threads > 0 ? o.block_threads : default_block;
-  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
-  while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
-    passes *= 2;
-    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
-  }
-  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  *U_out = U;
-  *t_out = t;
-  return KVQ_OK;
+  const bool wide = D % 4 == 0 && aligned(fp32_ptr, 16) && aligned(codes, 4) && aligned(scales, 16);
+  return stream_tiling(batch, N, D, wide ? 4 : 1, wide, default_unroll, default_block, U_out, t_out);
 }
 
 #define KVQ_LAUNCH8(KERNEL, ...)                                                                               \

@@ -41,6 +41,12 @@ struct Tiling {
 Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64_t target_blocks,
                    int block = kBlock, int passes = 0);
 
+// Launch shape of a streaming codec kernel (quantize / dequantize of any code format): lanes of V
+// channels, `default_unroll` rows in flight per lane and `default_block` threads unless the options
+// say otherwise, one-shot workgroups.  vector_lanes = false is the scalar fallback (one row at a time).
+kvq_status stream_tiling(int64_t batch, int64_t N, int64_t D, int V, bool vector_lanes, int default_unroll,
+                         int default_block, int* U_out, Tiling* t_out);
+
 struct Options {
   int codec_width = 4;
   int codec_unroll = 0;  // 0 = per kernel default (quantize 4, dequantize 2)
