@@ -452,6 +452,11 @@ def test_int4_hand_worked_and_packing():
     packed = oracle.pack_int4(q)
     assert packed.dtype == np.uint8 and packed.tolist() == [[0x97], [0x20], [0x22], [0x0E]]
     assert np.array_equal(oracle.unpack_int4(packed), q)
+    # the nibble 0x8 is -8 in two's complement (never produced by the quantizer, but part of the format)
+    assert oracle.unpack_int4(np.array([[0x88, 0x7F]], dtype=np.uint8)).tolist() == [[-8, -8, -1, 7]]
+    # a caller-given scale smaller than absmax / 7 clips at +-7
+    clip = oracle.quantize_q(np.array([[10.0], [-10.0], [7.4], [8.0]], dtype=np.float32), np.ones(1, np.float32), 7)
+    assert clip.ravel().tolist() == [7, -7, 7, 7]
     assert oracle.dequantize(q, s).tolist() == [[7.0, -14.0], [0.0, 4.0], [2.0, 4.0], [-2.0, 0.0]]
 
 
@@ -570,7 +575,8 @@ def test_fp8_encode_rounds_to_nearest_even_and_saturates():
     for lo, hi in zip(pos[:-1], pos[1:]):
         mid = (lo + hi) / 2
         cases += [mid, mid * (1 + Fraction(1, 2 ** 20)), mid * (1 - Fraction(1, 2 ** 20)), lo, hi]
-    cases += [Fraction(448), Fraction(449), Fraction(463), Fraction(464), Fraction(480), Fraction(10 ** 30),
+    cases += [Fraction(448), Fraction(449), Fraction(463), Fraction(464), Fraction(470), Fraction(479), Fraction(480),
+              Fraction(10 ** 30),
               Fraction(1, 1024), Fraction(1, 1025), Fraction(3, 2048), Fraction(1, 10 ** 30), Fraction(0)]
     y = np.array([float(v) for v in cases] + [-float(v) for v in cases], dtype=np.float32)
     got = oracle.fp8_encode(y)
