@@ -951,3 +951,24 @@ def test_fp8_special_scales_and_configs():
     q = fp8_round_trip(W.generate(2)[0])
     assert len(np.unique(q)) > 200
     fp8_round_trip(W.generate(3, slabs=(0, 24)))
+
+
+def test_matrix_core_scores_do_not_depend_on_the_launch_shape():
+    """Integer accumulation: the same slab gives the same bits whether it is scored alone or as one slab of a
+    larger batch (different token chunking per workgroup), and from run to run."""
+    rng = np.random.default_rng(91)
+    N, D, Q = 5000, 128, 8
+    x = make_matrix(rng, 3, N, D)
+    s = oracle.compute_scales(x)
+    codes = torch.from_numpy(oracle.quantize(x, s)).cuda()
+    scales = torch.from_numpy(s).cuda()
+    qs = torch.from_numpy(rng.standard_normal((3, Q, D)).astype(np.float32)).cuda()
+    out_all = torch.empty(3 * Q * N, dtype=torch.float32, device="cuda")
+    kvq.kvq_scores_from_codes(qs, Q, codes, scales, 3, N, D, out_all)
+    again = torch.empty_like(out_all)
+    kvq.kvq_scores_from_codes(qs, Q, codes, scales, 3, N, D, again)
+    assert torch.equal(out_all, again)
+    for b in range(3):
+        alone = torch.empty(Q * N, dtype=torch.float32, device="cuda")
+        kvq.kvq_scores_from_codes(qs[b].contiguous(), Q, codes[b].contiguous(), scales[b].contiguous(), 1, N, D, alone)
+        assert torch.equal(alone, out_all[b * Q * N:(b + 1) * Q * N])
