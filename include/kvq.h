@@ -236,7 +236,7 @@ kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
  *   scores_out[b,j,t] = sum_d queries[b,j,d] * ((float)codes[b,t,d] * scales[b,d])
  * The scale is folded into the query (qs = q*s, one fp32 rounding) and the codes are
  * used as read.  Two forms, chosen by shape:
- *  - Q >= 3, D % 64 == 0, D <= 1024, 16-byte aligned codes: int8 matrix cores.  qs is
+ *  - Q >= 3, D % 64 == 0, D <= 8192, 16-byte aligned codes: int8 matrix cores.  qs is
  *    taken to 28-bit fixed point relative to the largest |qs| of its query, the integer
  *    dot products are exact, the result is rounded once to fp32.  Against exact
  *    arithmetic: 2^-27 * max_d|queries*scales| * sum_d|codes|
@@ -248,7 +248,8 @@ kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
  *  Where q*s or the score falls below 2^-126 (fp32 gradual underflow) add (127 D + 1) * 2^-150.
  *   queries [batch,Q,D] fp32, codes [batch,N,D] int8, scales [batch,D] fp32:
  *   device, read only.  scores_out [batch,Q,N] fp32: device, written.
- * Any Q >= 1; 8 queries (16 on the matrix cores for D <= 512) are handled per pass over the codes.
+ * Any Q >= 1; queries per pass over the codes: 8 (fp32 form), 16 / 8 / 4 on the matrix cores for
+ * D <= 512 / 1024 / 8192.
  */
 kvq_status kvq_scores_from_codes(const float *queries, int64_t Q, const int8_t *codes,
                                  const float *scales, int64_t batch, int64_t N, int64_t D,

@@ -124,7 +124,26 @@ __global__ __launch_bounds__(kBlock) void scores_mfma_kernel(const float* __rest
             acc[u][g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[u][s], acc[u][g], 0, 0, 0);
         }
     } else {
-      for (int s = 0; s < steps; s++) {
+      // runtime number of steps: four at a time, so that every visit of a token's row fetches 256
+      // contiguous bytes (tokens of a tile lie in different DRAM pages once rows are long)
+      int s = 0;
+      for (; s + 4 <= steps; s += 4) {
+        v4i bv[TU][4];
+#pragma unroll
+        for (int u = 0; u < TU; u++)
+#pragma unroll
+          for (int k = 0; k < 4; k++) bv[u][k] = ld<NT>(reinterpret_cast<const v4i*>(row[u] + 64 * (s + k)));
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+#pragma unroll
+          for (int g = 0; g < G; g++) {
+            const v4i av = a_lds[((s + k) * G + g) * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < TU; u++)
+              acc[u][g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[u][k], acc[u][g], 0, 0, 0);
+          }
+      }
+      for (; s < steps; s++) {
         v4i bv[TU];
 #pragma unroll
         for (int u = 0; u < TU; u++) bv[u] = ld<NT>(reinterpret_cast<const v4i*>(row[u] + 64 * s));
@@ -158,6 +177,117 @@ __global__ __launch_bounds__(kBlock) void scores_mfma_kernel(const float* __rest
 #pragma unroll
       for (int u = 0; u < TU; u++)
         if (tl + kTileStride * u < t_end) st<NT_OUT>(po + kTileStride * u, v[u]);
+    }
+  }
+}
+
+// Rows wider than 1024 channels (up to 8192): four queries per pass, their digits for the whole row
+// resident in 128 KiB of LDS, one workgroup of 16 wavefronts per compute unit.  Wavefront w prepares
+// quarter w / 4 of query w % 4; the token loop is the one above with a runtime number of steps.
+constexpr int kWideBlock = 1024;
+constexpr int kWideMaxD = 8192;
+
+__global__ __launch_bounds__(kWideBlock) void scores_mfma_wide_kernel(const float* __restrict__ queries,
+                                                                      const int8_t* __restrict__ codes,
+                                                                      const float* __restrict__ scales,
+                                                                      float* __restrict__ out, int64_t N, int64_t D,
+                                                                      int64_t q_total, int64_t q_first, int q_count,
+                                                                      uint32_t chunks, int64_t tokens_per_chunk) {
+  __shared__ __align__(16) unsigned char dig[kWideMaxD * 16];  // [steps][64 lanes][16 bytes]
+  __shared__ double qscale[4];
+  __shared__ float red[16];
+  const int steps = (int)(D >> 6);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int64_t slab = blockIdx.x / chunks;
+  const int64_t t_begin = (int64_t)(blockIdx.x % chunks) * tokens_per_chunk;
+  int64_t t_end = t_begin + tokens_per_chunk;
+  if (t_end > N) t_end = N;
+  const float* ss = scales + slab * D;
+  const float* qb = queries + (slab * q_total + q_first) * D;
+
+  {
+    const int qi = wave & 3;
+    const bool live = qi < q_count;
+    const int64_t d_lo = (int64_t)(wave >> 2) * (D >> 2), d_hi = d_lo + (D >> 2);
+    float m = 0.0f;
+    if (live)
+      for (int64_t d = d_lo + lane; d < d_hi; d += 64) m = fmaxf(m, fabsf(qb[qi * D + d] * ss[d]));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[qi], red[qi + 4]), fmaxf(red[qi + 8], red[qi + 12]));
+    int E = 0;
+    (void)frexpf(m, &E);
+    const double up = ldexp(1.0, 27 - E);
+    if (wave < 4 && lane == 0) qscale[qi] = ldexp(1.0, E - 27);
+    for (int64_t d = d_lo + lane; d < d_hi; d += 64) {
+      int I = 0;
+      if (live) I = (int)rint((double)(qb[qi * D + d] * ss[d]) * up);
+      const int s = (int)(d >> 6), h = (int)(d >> 4) & 3, b = (int)d & 15;
+      unsigned char* p = dig + ((size_t)s * 64 + 16 * h + 4 * qi) * 16 + b;
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const int pj = ((I + 64) & 127) - 64;
+        const int dj = j < 3 ? pj : I;
+        p[16 * j] = (unsigned char)(dj & 0xff);
+        I = (I - pj) >> 7;
+      }
+    }
+  }
+  __syncthreads();
+
+  const int n = lane & 15, h = lane >> 4;
+  const v4i* a_lds = reinterpret_cast<const v4i*>(dig);
+  const int8_t* cs = codes + slab * N * D + 16 * h;
+  float* os = out + (slab * q_total + q_first) * N;
+  const bool vec_store = (N & 1) == 0 && (reinterpret_cast<uintptr_t>(out) & 7) == 0;
+  // A wavefront takes TW tiles of 16 tokens and walks the row SU steps (SU * 64 channels) at a time, so
+  // that every visit of a token's row fetches SU * 64 contiguous bytes: with rows of several KiB the
+  // tokens of a tile lie in different DRAM pages, and short visits would reopen them over and over.
+  constexpr int TW = 2, SU = 4;
+  for (int64_t t0 = t_begin + (int64_t)wave * (16 * TW); t0 < t_end; t0 += (kWideBlock / 64) * 16 * TW) {
+    v4i acc[TW];
+    const int8_t* row[TW];
+#pragma unroll
+    for (int u = 0; u < TW; u++) {
+      int64_t t = t0 + TW * n + u;  // a lane's tiles are consecutive tokens
+      if (t >= t_end) t = t_end - 1;
+      row[u] = cs + t * D;
+      acc[u] = v4i{0, 0, 0, 0};
+    }
+    for (int s = 0; s < steps; s += SU) {  // steps is a multiple of 4: D % 256 == 0 on this path
+      v4i bv[TW][SU];
+#pragma unroll
+      for (int u = 0; u < TW; u++)
+#pragma unroll
+        for (int k = 0; k < SU; k++) bv[u][k] = *reinterpret_cast<const v4i*>(row[u] + 64 * (s + k));
+#pragma unroll
+      for (int k = 0; k < SU; k++) {
+        const v4i av = a_lds[(s + k) * 64 + lane];
+#pragma unroll
+        for (int u = 0; u < TW; u++) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[u][k], acc[u], 0, 0, 0);
+      }
+    }
+    const int qi = h;
+    if (qi >= q_count) continue;
+    const int64_t tl = t0 + TW * n;
+    float v[TW];
+#pragma unroll
+    for (int u = 0; u < TW; u++) {
+      const int64_t S = (int64_t)acc[u][0] + (int64_t)acc[u][1] * 128 + (int64_t)acc[u][2] * 16384 +
+                        (int64_t)acc[u][3] * 2097152;
+      v[u] = (float)((double)S * qscale[qi]);
+    }
+    float* po = os + qi * N + tl;
+    if (vec_store && tl + 2 <= t_end) {
+      __builtin_nontemporal_store(f32x2{v[0], v[1]}, reinterpret_cast<f32x2*>(po));
+    } else {
+#pragma unroll
+      for (int u = 0; u < TW; u++)
+        if (tl + u < t_end) po[u] = v[u];
     }
   }
 }
@@ -198,7 +328,7 @@ kvq_status launch_steps(const float* queries, const int8_t* codes, const float* 
     return launch_g<G, 2, 4>(queries, codes, scales, out, batch, N, D, q_total, q_first, q_count, cus, lds_bytes, stream);
   if (D == 256)
     return launch_g<G, 4, 2>(queries, codes, scales, out, batch, N, D, q_total, q_first, q_count, cus, lds_bytes, stream);
-  return launch_g<G, 0, 4>(queries, codes, scales, out, batch, N, D, q_total, q_first, q_count, cus, lds_bytes, stream);
+  return launch_g<G, 0, 2>(queries, codes, scales, out, batch, N, D, q_total, q_first, q_count, cus, lds_bytes, stream);
 }
 
 }  // namespace
@@ -206,14 +336,30 @@ kvq_status launch_steps(const float* queries, const int8_t* codes, const float* 
 bool scores_mfma_applicable(const float* queries, int64_t Q, const int8_t* codes, const float* scales, int64_t D) {
   (void)queries;
   (void)scales;
-  // 16-byte code loads of whole 64-channel steps; digits of 8 queries in 32 KiB of LDS
-  return Q >= 3 && D % 64 == 0 && D <= 1024 && aligned(codes, 16);
+  // 16-byte code loads of whole 64-channel steps; digits of 8-16 queries in 32 KiB of LDS up to 1024
+  // channels, of 4 queries in 128 KiB up to 8192 channels (quarters of a row must be whole 16-byte pieces)
+  return Q >= 3 && D % 64 == 0 && (D <= 1024 || (D % 256 == 0 && D <= kWideMaxD)) && aligned(codes, 16);
 }
 
 kvq_status launch_scores_mfma(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
                               int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  if (D > 1024) {
+    // one workgroup per compute unit; whole passes of 16 wavefronts x 4 tiles of 16 tokens
+    const int64_t pass = (kWideBlock / 64) * 16 * 2;
+    int64_t per = (batch * N + dev.cus - 1) / dev.cus;
+    per = (per + pass - 1) / pass * pass;
+    const int64_t chunks = (N + per - 1) / per;
+    if (batch * chunks > INT32_MAX) return KVQ_ERR_OVERFLOW;
+    for (int64_t q0 = 0; q0 < Q; q0 += 4) {
+      const int qc = (int)(Q - q0 < 4 ? Q - q0 : 4);
+      hipLaunchKernelGGL(scores_mfma_wide_kernel, dim3((uint32_t)(batch * chunks)), dim3(kWideBlock), 0, stream, queries,
+                         codes, scales, out, N, D, Q, q0, qc, (uint32_t)chunks, per);
+      KVQ_HIP(hipGetLastError());
+    }
+    return KVQ_OK;
+  }
   const int64_t per_pass = D <= 512 ? 16 : 8;  // queries per pass over the codes (digits within 32 KiB of LDS)
   for (int64_t q0 = 0; q0 < Q; q0 += per_pass) {
     const int qc = (int)(Q - q0 < per_pass ? Q - q0 : per_pass);

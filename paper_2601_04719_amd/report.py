@@ -217,7 +217,7 @@ def main():
                 out = torch.empty(B * Q * N, device="cuda")
                 m, _ = timeit(lambda: kvq.kvq_scores_from_codes(q, Q, codes, scales, B, N, D, out))
                 nbytes = E + 4.0 * B * Q * N + 4.0 * B * Q * D + 4.0 * B * D
-                kind = "int8 MFMA" if (Q >= 3 and D % 64 == 0 and D <= 1024) else "fp32 FMA"
+                kind = "int8 MFMA" if (Q >= 3 and D % 64 == 0 and (D <= 1024 or (D % 256 == 0 and D <= 8192))) else "fp32 FMA"
                 print("| %d x %d x %d | %d | %s | %.4f | %.4f | %.0f | %.3f | %.1f |" % (
                     B, N, D, Q, kind, m, nbytes / 1e9, nbytes / m / 1e6, nbytes / m / 1e6 / 8000.0, 2.0 * Q * E / m / 1e9))
                 sys.stdout.flush()

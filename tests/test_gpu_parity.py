@@ -330,7 +330,7 @@ def check_scores(x, qs, Q, offset=0):
     kvq.kvq_scores_from_codes(qd, Q, g.codes, g.scales, batch, N, D, out)
     got = out[:batch * Q * N].cpu().numpy().reshape(batch, Q, N).astype(np.float64)
     assert bool((out[batch * Q * N:] == 555.0).all())
-    matrix_cores = Q >= 3 and D % 64 == 0 and D <= 1024 and offset % 16 == 0
+    matrix_cores = Q >= 3 and D % 64 == 0 and (D <= 1024 or (D % 256 == 0 and D <= 8192)) and offset % 16 == 0
     fast = D % 16 == 0 and offset % 16 == 0
     worst = 0.0
     for b in range(batch):
