@@ -236,7 +236,8 @@ kvq_status kvq_attn_score_error(const float *queries, int64_t Q,
  *   scores_out[b,j,t] = sum_d queries[b,j,d] * ((float)codes[b,t,d] * scales[b,d])
  * The scale is folded into the query (qs = q*s, one fp32 rounding) and the codes are
  * used as read.  Two forms, chosen by shape:
- *  - Q >= 3, D % 64 == 0, D <= 8192, 16-byte aligned codes: int8 matrix cores.  qs is
+ *  - Q >= 3, 16-byte aligned codes, and D % 64 == 0 up to 1024 or D % 256 == 0 up to
+ *    8192: int8 matrix cores.  qs is
  *    taken to 28-bit fixed point relative to the largest |qs| of its query, the integer
  *    dot products are exact, the result is rounded once to fp32.  Against exact
  *    arithmetic: 2^-27 * max_d|queries*scales| * sum_d|codes|

@@ -127,7 +127,7 @@ kvq_status launch_probe_codec(int mode, const float* src_f32, float* dst_f32, co
                               hipStream_t stream);
 kvq_status launch_scores_from_codes(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
                                     int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream);
-// Matrix-core form of the same for Q >= 3 (D % 64 == 0, D <= 8192, 16-byte aligned codes).
+// Matrix-core form of the same for Q >= 3 (16-byte aligned codes; D % 64 == 0 up to 1024, D % 256 == 0 up to 8192).
 bool scores_mfma_applicable(const float* queries, int64_t Q, const int8_t* codes, const float* scales, int64_t D);
 kvq_status launch_scores_mfma(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
                               int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream);
