@@ -257,6 +257,20 @@ kvq_status kvq_scores_from_codes(const float *queries, int64_t Q, const int8_t *
                                  float *scores_out, kvq_stream_t stream);
 
 /*
+ * kvq_scores_from_codes for a 4-bit cache (kvq_quantize_int4's packed layout, scales =
+ * absmax / 7): scores_out[b,j,t] = sum_d queries[b,j,d] * ((float)code[b,t,d] * scales[b,d])
+ * with code in [-7, 7].  D must be even (KVQ_ERR_ARG otherwise).  D % 128 == 0, D <= 1024
+ * and 16-byte aligned packed rows run on the int8 matrix cores with the error bound of the
+ * 8-bit matrix-core form; any other shape takes a scalar fp32 kernel with the bound
+ * (D + 4) * 2^-24 * sum_d |queries * codes * scales|.
+ *   queries [batch,Q,D] fp32, packed [batch,N,D/2] uint8, scales [batch,D] fp32: device,
+ *   read only.  scores_out [batch,Q,N] fp32: device, written.
+ */
+kvq_status kvq_scores_from_codes_int4(const float *queries, int64_t Q, const uint8_t *packed,
+                                      const float *scales, int64_t batch, int64_t N, int64_t D,
+                                      float *scores_out, kvq_stream_t stream);
+
+/*
  * Measurement aid: no-math streaming kernels, to find what this GPU's memory
  * system sustains for the library's traffic patterns over a [batch,N,D] problem.
  *   mode 0: read the fp32 matrix src_f32                  (4 B/element; flat one-shot kernel)

@@ -307,6 +307,18 @@ kvq_status kvq_scores_from_codes(const float* queries, int64_t Q, const int8_t* 
   return launch_scores_from_codes(queries, Q, codes, scales, batch, N, D, scores_out, stream);
 }
 
+kvq_status kvq_scores_from_codes_int4(const float* queries, int64_t Q, const uint8_t* packed, const float* scales,
+                                      int64_t batch, int64_t N, int64_t D, float* scores_out, kvq_stream_t stream) {
+  if (!queries || !packed || !scales || !scores_out) return KVQ_ERR_NULL;
+  if (Q < 1) return KVQ_ERR_SHAPE;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (D % 2) return KVQ_ERR_ARG;
+  if (Q > INT32_MAX || Q > (INT64_MAX / 8) / D || batch > (INT64_MAX / 8) / (Q * D) || Q > (INT64_MAX / 8) / N ||
+      batch > (INT64_MAX / 8) / (Q * N))
+    return KVQ_ERR_OVERFLOW;
+  return launch_scores_from_codes_int4(queries, Q, packed, scales, batch, N, D, scores_out, stream);
+}
+
 const char* kvq_status_string(kvq_status status) {
   switch (status) {
     case KVQ_OK: return "KVQ_OK";

@@ -131,6 +131,9 @@ kvq_status launch_scores_from_codes(const float* queries, int64_t Q, const int8_
 bool scores_mfma_applicable(const float* queries, int64_t Q, const int8_t* codes, const float* scales, int64_t D);
 kvq_status launch_scores_mfma(const float* queries, int64_t Q, const int8_t* codes, const float* scales,
                               int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream);
+// Scores from a 4-bit cache (packed rows of D / 2 bytes, D even).
+kvq_status launch_scores_from_codes_int4(const float* queries, int64_t Q, const uint8_t* packed, const float* scales,
+                                         int64_t batch, int64_t N, int64_t D, float* out, hipStream_t stream);
 kvq_status launch_absmax_scales_16(int dtype, const void* x, float* scales, int64_t batch, int64_t N, int64_t D,
                                    hipStream_t stream);
 kvq_status launch_quantize_16(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,

@@ -25,7 +25,7 @@ EXPORTS = (
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
     "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
-    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_probe_stream", "kvq_status_string",
+    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
 )
 
@@ -75,6 +75,8 @@ def lib():
         L.kvq_quantize_variant.restype = i32
         L.kvq_scores_from_codes.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
         L.kvq_scores_from_codes.restype = i32
+        L.kvq_scores_from_codes_int4.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
+        L.kvq_scores_from_codes_int4.restype = i32
         L.kvq_probe_stream.argtypes = [i32, p, p, p, p, p, i64, i64, i64, p]
         L.kvq_probe_stream.restype = i32
         L.kvq_roundtrip_error.argtypes = [p, p, p, p, i64, i64, i64, p, p, p]
@@ -212,6 +214,11 @@ def kvq_attn_score_error(queries, Q, k, k_hat, codes, scales, N, D, mean_abs_out
 def kvq_scores_from_codes(queries, Q, codes, scales, batch, N, D, scores_out, stream=None):
     _check(lib().kvq_scores_from_codes(_addr(queries), Q, _addr(codes), _addr(scales), batch, N, D,
                                        _addr(scores_out), _stream(stream)), "kvq_scores_from_codes")
+
+
+def kvq_scores_from_codes_int4(queries, Q, packed, scales, batch, N, D, scores_out, stream=None):
+    _check(lib().kvq_scores_from_codes_int4(_addr(queries), Q, _addr(packed), _addr(scales), batch, N, D,
+                                            _addr(scores_out), _stream(stream)), "kvq_scores_from_codes_int4")
 
 
 def kvq_probe_stream(mode, src_f32, dst_f32, src_i8, dst_i8, scales, batch, N, D, stream=None):

@@ -6,6 +6,7 @@ Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
         python -m paper_2601_04719_amd.report --append           (streaming append onto an int8 cache)
         python -m paper_2601_04719_amd.report --graph            (small configurations: eager launches vs one HIP graph)
         python -m paper_2601_04719_amd.report --fp8              (FP8 E4M3 codes)
+        python -m paper_2601_04719_amd.report --scores-int4      (attention scores straight from a 4-bit cache)
         python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
         python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
@@ -30,6 +31,7 @@ def main():
     ap.add_argument("--append", action="store_true", help="kvq_append: decode steps and prefill chunks")
     ap.add_argument("--graph", action="store_true", help="launch-bound configurations: eager step vs graph replay")
     ap.add_argument("--fp8", action="store_true", help="FP8 (E4M3) codes: absmax, quantize, dequantize, errors")
+    ap.add_argument("--scores-int4", action="store_true", help="kvq_scores_from_codes_int4 on decode-like shapes")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
@@ -201,6 +203,25 @@ def main():
             print("| %s | %s | %s | %s | %.4g | %.4g |" % (c.name, cell(ta, 4.0), cell(tq, 4.5), cell(td, 4.5), e4, e8))
             sys.stdout.flush()
             del x, xh, packed, codes
+            torch.cuda.empty_cache()
+        return
+
+    if args.scores_int4:
+        print("| batch x N x D | Q | mean ms | bytes moved (GB) | GB/s | of 8 TB/s | tokens scored per second (G) |")
+        print("|---|---|---|---|---|---|---|")
+        for (B, N, D) in [(256, 4096, 128), (2048, 4096, 128), (32, 131072, 128), (512, 4096, 256)]:
+            E = B * N * D
+            packed = torch.randint(0, 256, (E // 2,), dtype=torch.uint8, device="cuda")
+            scales = torch.rand(B * D, device="cuda") + 0.1
+            for Q in (1, 2, 4, 8, 16):
+                q = torch.randn(B * Q * D, device="cuda")
+                out = torch.empty(B * Q * N, device="cuda")
+                m, _ = timeit(lambda: kvq.kvq_scores_from_codes_int4(q, Q, packed, scales, B, N, D, out))
+                nbytes = E / 2 + 4.0 * B * Q * N + 4.0 * B * Q * D + 4.0 * B * D
+                print("| %d x %d x %d | %d | %.4f | %.4f | %.0f | %.3f | %.1f |" % (
+                    B, N, D, Q, m, nbytes / 1e9, nbytes / m / 1e6, nbytes / m / 1e6 / 8000.0, B * N / m / 1e6))
+                sys.stdout.flush()
+            del packed
             torch.cuda.empty_cache()
         return
 

@@ -972,3 +972,50 @@ def test_matrix_core_scores_do_not_depend_on_the_launch_shape():
         alone = torch.empty(Q * N, dtype=torch.float32, device="cuda")
         kvq.kvq_scores_from_codes(qs[b].contiguous(), Q, codes[b].contiguous(), scales[b].contiguous(), 1, N, D, alone)
         assert torch.equal(alone, out_all[b * Q * N:(b + 1) * Q * N])
+
+
+# ------------------------------------------------------------------ scores from a 4-bit cache
+@pytest.mark.parametrize("shape,Q,offset", [((6, 1000, 128), 8, 0), ((1, 4096, 128), 1, 0), ((3, 257, 256), 5, 0),
+                                            ((2, 100, 1024), 3, 0), ((1, 300, 64), 4, 0), ((1, 70, 20), 2, 0),
+                                            ((2, 515, 128), 16, 0), ((1, 333, 512), 13, 0), ((2, 64, 128), 7, 8),
+                                            ((3, 1, 128), 8, 0), ((1, 50, 2048), 3, 0)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_scores_from_a_four_bit_cache(shape, Q, offset):
+    batch, N, D = shape
+    rng = np.random.default_rng(N + D + Q)
+    x = make_matrix(rng, batch, N, D)
+    qs = rng.standard_normal((batch, Q, D)).astype(np.float32)
+    qs[:, 0] *= 1e-3
+    s_ref = oracle.compute_scales_q(x, 7).reshape(batch, D)
+    q_ref = oracle.quantize_q(x, s_ref, 7)
+    packed_np = oracle.pack_int4(q_ref)
+    buf = torch.zeros(packed_np.size + 64, dtype=torch.uint8, device="cuda")
+    packed = buf[offset:offset + packed_np.size]
+    packed.copy_(torch.from_numpy(packed_np.reshape(-1)))
+    scales = torch.from_numpy(s_ref).cuda()
+    out = torch.full((batch * Q * N + 8,), 555.0, dtype=torch.float32, device="cuda")
+    kvq.kvq_scores_from_codes_int4(torch.from_numpy(qs).cuda(), Q, packed, scales, batch, N, D, out)
+    got = out[:batch * Q * N].cpu().numpy().reshape(batch, Q, N).astype(np.float64)
+    assert bool((out[batch * Q * N:] == 555.0).all())
+    matrix_cores = D % 128 == 0 and D <= 1024 and offset % 16 == 0
+    for b in range(batch):
+        ref = oracle.scores_from_codes(qs[b], q_ref[b], s_ref[b])
+        xh = oracle.dequantize(q_ref[b], s_ref[b]).astype(np.float64)
+        mag = np.abs(qs[b].astype(np.float64)) @ np.abs(xh).T
+        if matrix_cores:
+            top = np.abs(qs[b].astype(np.float64) * s_ref[b].astype(np.float64)).max(axis=1) * (1 + 2.0 ** -23)
+            bound = 2.0 ** -27 * top[:, None] * np.abs(q_ref[b].astype(np.float64)).sum(axis=1)[None, :] \
+                + 4 * 2.0 ** -24 * mag
+        else:
+            bound = scores_bound(D, False) * mag
+        bound = bound + (127 * D + 1) * 2.0 ** -150
+        err = np.abs(got[b] - ref)
+        assert (err <= bound).all(), (b, float((err / bound).max()))
+
+
+def test_scores_int4_rejects_an_odd_channel_count():
+    z = torch.zeros(64, dtype=torch.float32, device="cuda")
+    p = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.kvq_scores_from_codes_int4(z, 1, p, z, 1, 3, 5, z)
+    assert e.value.status == kvq.ERR_ARG
