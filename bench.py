@@ -96,6 +96,13 @@ def time_extras(kvq, torch, stream, h, x, x_hat, codes, scales, E, N, D):
         nbytes = E + 4.0 * B * Q * 4096 + 4.0 * B * Q * 128 + 4.0 * B * 128
         out["scores_from_codes_Q%d" % Q] = row(t(lambda: kvq.kvq_scores_from_codes(q, Q, codes, s2, B, 4096, 128, o,
                                                                                 stream=h)), nbytes)
+    p4 = u8[:E // 2]                                    # any bytes are valid packed 4-bit codes
+    for Q in (1, 8):
+        q = torch.randn(B * Q * 128, device=x.device)
+        o = torch.empty(B * Q * 4096, device=x.device)
+        nbytes = E / 2 + 4.0 * B * Q * 4096 + 4.0 * B * Q * 128 + 4.0 * B * 128
+        out["scores_from_codes_int4_Q%d" % Q] = row(t(lambda: kvq.kvq_scores_from_codes_int4(q, Q, p4, s2, B, 4096, 128, o,
+                                                                                          stream=h)), nbytes)
     tok = (torch.rand(B, 1, 128, device=x.device) - 0.5) * s2.view(B, 1, 128) * 100.0   # inside the range: no growth
     s3 = s2.clone()
     ms = t(lambda: kvq.kvq_append(tok, s3, prev, codes, B, 4095, 1, 4096, 128, stream=h))
