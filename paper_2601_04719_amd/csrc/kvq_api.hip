@@ -87,14 +87,15 @@ Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64
 }
 
 kvq_status stream_tiling(int64_t batch, int64_t N, int64_t D, int V, bool vector_lanes, int default_unroll,
-                         int default_block, int* U_out, Tiling* t_out) {
+                         int default_block, int* U_out, Tiling* t_out, int default_passes) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options o = options();
   int U = o.codec_unroll > 0 ? o.codec_unroll : default_unroll;
   if (!vector_lanes) U = 1;
   else if (V > 4 && U > 4) U = 4;
-  int passes = o.passes_per_block;
+  // the passes option, when moved off its default of 1, overrides a kernel's own default
+  int passes = o.passes_per_block != 1 ? o.passes_per_block : default_passes;
   const int block = o.block_threads > 0 ? o.block_threads : default_block;
   Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
   // one-shot workgroups by default; fall back to longer walks only when the grid would not be indexable

@@ -45,7 +45,7 @@ Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64
 // channels, `default_unroll` rows in flight per lane and `default_block` threads unless the options
 // say otherwise, one-shot workgroups.  vector_lanes = false is the scalar fallback (one row at a time).
 kvq_status stream_tiling(int64_t batch, int64_t N, int64_t D, int V, bool vector_lanes, int default_unroll,
-                         int default_block, int* U_out, Tiling* t_out);
+                         int default_block, int* U_out, Tiling* t_out, int default_passes = 1);
 
 struct Options {
   int codec_width = 4;
