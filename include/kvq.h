@@ -21,10 +21,12 @@
  *  - argument errors are detected on the host before anything is enqueued and
  *    reported as a negative status with no side effects; a failed HIP call maps
  *    to KVQ_ERR_HIP.  Input and output buffers must not overlap.
- *  - kvq_roundtrip_error and kvq_attn_score_error keep a small per-device,
- *    per-stream workspace (partial sums) that the library allocates on first use;
- *    two calls in flight on the SAME stream are ordered by the stream, calls on
- *    different streams use different workspaces.
+ *  - the scale reductions (kvq_absmax_scales and its _t, _int4, _fp8 forms),
+ *    kvq_roundtrip_error and kvq_attn_score_error keep a per-device, per-stream
+ *    workspace (16 MiB of partial maxima and sums) that the library allocates with
+ *    hipMalloc on a stream's first such call and never frees -- make that call
+ *    outside any graph capture.  Two calls in flight on the SAME stream are
+ *    ordered by the stream; calls on different streams use different workspaces.
  *  - results of kvq_absmax_scales, kvq_quantize, kvq_dequantize are unique bit
  *    patterns; the error statistics are deterministic for a given shape.
  */

@@ -5,33 +5,55 @@
 // streaming reduction over rows: every lane owns V adjacent channels, reads
 // its rows with 16-byte loads that a wavefront issues as whole contiguous row
 // segments, keeps V running maxima in registers, and at the end the maxima of
-// the lanes that share channels are combined in LDS and merged across
-// workgroups with an atomic max on the bit pattern of the (non-negative)
-// float, whose unsigned order equals the float order.  max is associative and
-// commutative, so the result does not depend on the launch shape.
+// the lanes that share channels are combined in LDS.  A workgroup that saw
+// every row of its slab divides and writes the scales itself; otherwise it
+// stores its maxima to its row chunk's slot of a workspace with plain vector
+// stores and a small second kernel takes the maximum over the chunks and
+// divides.  (Merging with one atomic max per channel and workgroup instead
+// costs about 80 ns per workgroup once the channels fall into a few cache
+// lines -- 20 us of a 26 us call on [32768 x 128] -- and needs the scale
+// buffer cleared first.)  max is associative and commutative, so the result
+// does not depend on the launch shape.
 //
 // Unlike the codec kernels, workgroups here walk long row chunks: one workgroup
 // per compute unit, each lane owning up to 8 column groups so that the workgroup
 // reads whole rows -- one fat contiguous stream per compute unit.  Measured on
 // the 1B-element shape: 7.0 TB/s, against 6.5 TB/s with eight 4 KiB-wide
 // workgroups per compute unit, and 4 TB/s for one-shot workgroups of a few rows
-// (each ending in an atomic per channel).
+// (each ending in a store per channel).
 #include <type_traits>
 
 #include "kvq_internal.h"
 
 namespace kvq {
 
-__global__ __launch_bounds__(kBlock) void fill_zero_u32(uint32_t* p, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n) p[i] = 0u;
-}
-
-// One IEEE fp32 divide per channel, in place over the max bit patterns.
-// qmax = 127 (8-bit codes) or 7 (4-bit codes).
-__global__ __launch_bounds__(kBlock) void finalize_scales(float* scales, int64_t n, float qmax) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n) scales[i] = scales[i] / qmax;
+// Second stage: scales[i] = max over row chunks of colmax[r * total + i], then one IEEE fp32 divide
+// by qmax (127 for 8-bit codes, 7 for 4-bit codes, 448 for FP8).  A workgroup owns kFinX adjacent
+// channels; its kFinY lanes per channel split the row chunks and meet in LDS.
+constexpr int kFinX = 16, kFinY = kBlock / kFinX;
+__global__ __launch_bounds__(kBlock) void absmax_finalize_kernel(const float* __restrict__ colmax,
+                                                                 float* __restrict__ scales, int64_t total,
+                                                                 uint32_t rchunks, float qmax) {
+  __shared__ float red[kBlock];
+  const int tx = threadIdx.x % kFinX, ty = threadIdx.x / kFinX;
+  const int64_t i = (int64_t)blockIdx.x * kFinX + tx;
+  float m = 0.0f;
+  if (i < total) {
+    const float* p = colmax + i;
+    uint32_t r = ty;
+    for (; r + 3 * kFinY < rchunks; r += 4 * kFinY) {
+      const float a = p[(int64_t)r * total], b = p[(int64_t)(r + kFinY) * total];
+      const float c = p[(int64_t)(r + 2 * kFinY) * total], d = p[(int64_t)(r + 3 * kFinY) * total];
+      m = fmaxf(fmaxf(m, fmaxf(a, b)), fmaxf(c, d));
+    }
+    for (; r < rchunks; r += kFinY) m = fmaxf(m, p[(int64_t)r * total]);
+  }
+  red[threadIdx.x] = m;
+  __syncthreads();
+  if (ty == 0 && i < total) {
+    for (int y = 1; y < kFinY; y++) m = fmaxf(m, red[y * kFinX + tx]);
+    scales[i] = m / qmax;
+  }
 }
 
 // |v| joins the running maximum only when strictly larger, as in the algorithm;
@@ -41,8 +63,8 @@ __device__ __forceinline__ float absmax_step(float m, float v) { return fmaxf(m,
 // A lane owns J groups of V adjacent channels, TX groups apart: with J * TX * V
 // >= D a workgroup reads whole rows, i.e. one contiguous stream per workgroup.
 template <int V, int J, int U, bool NT>
-__global__ __launch_bounds__(kBlock) void absmax_kernel(const float* __restrict__ x,
-                                                        uint32_t* __restrict__ max_bits, int64_t N, int64_t D,
+__global__ __launch_bounds__(kBlock) void absmax_kernel(const float* __restrict__ x, float* __restrict__ dst,
+                                                        int64_t chunk_stride, float qmax, int64_t N, int64_t D,
                                                         int tx_log2, uint32_t ctiles, uint32_t rchunks,
                                                         int64_t rows_per_chunk, int64_t groups) {
   __shared__ float red[J == 1 ? kBlock * V : 1];
@@ -101,7 +123,7 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const float* __restrict_
   }
 
   // combine the TY lanes that share a channel group (LDS; only rows narrower than a workgroup
-  // have TY > 1, and those use J == 1), then one atomic per channel
+  // have TY > 1, and those use J == 1)
   if constexpr (J == 1) {
     if (it.TY > 1) {
 #pragma unroll
@@ -115,30 +137,38 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const float* __restrict_
       }
     }
   }
+  // rchunks == 1: dst is the scale buffer and this workgroup has the final maxima;
+  // otherwise dst is the workspace, [row chunk][batch * D], and chunk_stride = batch * D
   if (it.ty == 0) {
+    const bool final_pass = rchunks == 1;
+    const uint32_t rc = (blockIdx.x / ctiles) % rchunks;
 #pragma unroll
     for (int j = 0; j < J; j++) {
       if (!act[j]) continue;
-      uint32_t* out = max_bits + it.slab * D + (group0 + (int64_t)j * TX) * V;
+      float* out = dst + (int64_t)rc * chunk_stride + it.slab * D + (group0 + (int64_t)j * TX) * V;
+      if (final_pass) {
 #pragma unroll
-      for (int i = 0; i < V; i++) {
-        const uint32_t bits = __float_as_uint(m[j][i]);
-        if (bits != 0u) atomicMax(out + i, bits);
+        for (int i = 0; i < V; i++) out[i] = m[j][i] / qmax;
+      } else if constexpr (V == 4) {
+        *reinterpret_cast<f32x4*>(out) = f32x4{m[j][0], m[j][1], m[j][2], m[j][3]};
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; i++) out[i] = m[j][i];
       }
     }
   }
 }
 
 template <int V, int J, int U>
-static kvq_status launch_absmax_t(const float* x, uint32_t* bits, int64_t N, int64_t D, const Tiling& t,
-                                  bool nt, hipStream_t stream) {
+static kvq_status launch_absmax_t(const float* x, float* dst, int64_t chunk_stride, float qmax, int64_t N,
+                                  int64_t D, const Tiling& t, bool nt, hipStream_t stream) {
   const dim3 grid((uint32_t)t.items), block(kBlock);
   if (nt)
-    hipLaunchKernelGGL((absmax_kernel<V, J, U, true>), grid, block, 0, stream, x, bits, N, D, t.tx_log2,
-                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+    hipLaunchKernelGGL((absmax_kernel<V, J, U, true>), grid, block, 0, stream, x, dst, chunk_stride, qmax, N, D,
+                       t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
   else
-    hipLaunchKernelGGL((absmax_kernel<V, J, U, false>), grid, block, 0, stream, x, bits, N, D, t.tx_log2,
-                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+    hipLaunchKernelGGL((absmax_kernel<V, J, U, false>), grid, block, 0, stream, x, dst, chunk_stride, qmax, N, D,
+                       t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }
@@ -149,17 +179,16 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options& o = options();
   const int V = (D % 4 == 0 && aligned(x, 16)) ? 4 : 1;
-  // J column groups per lane: as many as it takes for a workgroup to span whole rows, at most 8 --
-  // but a wider workgroup means more row chunks for the same number of workgroups, and every chunk
-  // ends in one atomic per channel.  Keep at least about 512 rows per workgroup: measured on
-  // [16384 x 8192] J = 1 / 4 / 8 give 5.9 / 5.7 / 5.3 TB/s, on [4096 x 8192] 3.6 / 3.5 / 2.6, while
-  // from [65536 x 8192] up the wide forms win (6.3 / 6.8 / 6.8; 7.0 for J = 8 at 131072 rows).
+  // J column groups per lane: as many as it takes for a workgroup to span whole rows, at most 8.
+  // Measured on D = 8192 (J = 1 / 4 / 8, one workgroup per compute unit): 4096 rows 37 / 30 / 35 us,
+  // 16384 rows 85.6 / 84.6 / 86.4 us, 65536 rows 337 / 312 / 313 us, 131072 rows 700 / 663 / 610 us:
+  // 4 up to about 2^30 elements, 8 from there.
   int J = 1;
   if (V == 4) {
     const int64_t groups = D / 4;
     const int64_t elements = batch * N * D;
-    const int64_t j_rows = elements / ((int64_t)dev.cus << 19);  // 512 rows x 1024 channels per unit of J
-    while (J < o.absmax_span && J * 2 <= j_rows && (int64_t)kBlock * J < groups) J *= 2;
+    const int jmax = elements >= ((int64_t)dev.cus << 22) ? 8 : 4;
+    while (J < o.absmax_span && J < jmax && (int64_t)kBlock * J < groups) J *= 2;
   }
   // rows in flight: J * U 16-byte loads per lane, at most 16
   int U = o.absmax_unroll;
@@ -180,16 +209,17 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
     t.ctiles = (uint32_t)((t.groups + (int64_t)kBlock * J - 1) / ((int64_t)kBlock * J));
     t.items = batch * (int64_t)t.rchunks * t.ctiles;
   }
-  const int64_t n_scales = batch * D;
-  const int64_t small_blocks = (n_scales + kBlock - 1) / kBlock;
-  if (small_blocks > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  uint32_t* bits = reinterpret_cast<uint32_t*>(scales);
-
-  hipLaunchKernelGGL(fill_zero_u32, dim3((uint32_t)small_blocks), dim3(kBlock), 0, stream, bits, n_scales);
-  KVQ_HIP(hipGetLastError());
+  const int64_t total = batch * D;
+  limit_row_chunks(&t, batch, N, absmax_chunk_cap(total));
+  float* dst = scales;
+  if (t.rchunks > 1) {
+    Workspace ws;
+    if (kvq_status s = get_workspace(stream, &ws)) return s;
+    dst = ws.colmax;
+  }
   const bool nt = o.nontemporal != 0;
   kvq_status s;
-#define KVQ_AM(V_, J_, U_) s = launch_absmax_t<V_, J_, U_>(x, bits, N, D, t, nt, stream)
+#define KVQ_AM(V_, J_, U_) s = launch_absmax_t<V_, J_, U_>(x, dst, total, qmax, N, D, t, nt, stream)
   if (V == 4 && J == 8 && U == 4) KVQ_AM(4, 8, 4);
   else if (V == 4 && J == 8) KVQ_AM(4, 8, 2);
   else if (V == 4 && J == 4 && U == 4) KVQ_AM(4, 4, 4);
@@ -204,9 +234,28 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   else KVQ_AM(1, 1, 16);
 #undef KVQ_AM
   if (s != KVQ_OK) return s;
-  hipLaunchKernelGGL(finalize_scales, dim3((uint32_t)small_blocks), dim3(kBlock), 0, stream, scales, n_scales, qmax);
+  if (t.rchunks > 1) return launch_absmax_finalize(dst, scales, total, t.rchunks, qmax, stream);
+  return KVQ_OK;
+}
+
+kvq_status launch_absmax_finalize(const float* colmax, float* scales, int64_t total, uint32_t rchunks, float qmax,
+                                  hipStream_t stream) {
+  const int64_t blocks = (total + kFinX - 1) / kFinX;
+  if (blocks > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  hipLaunchKernelGGL(absmax_finalize_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, colmax, scales, total,
+                     rchunks, qmax);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
+}
+
+void limit_row_chunks(Tiling* t, int64_t batch, int64_t N, int64_t cap) {
+  if (cap < 1) cap = 1;
+  if ((int64_t)t->rchunks <= cap) return;
+  // keep rows_per_chunk a multiple of what it already is a multiple of: scale it by a whole factor
+  const int64_t factor = ((int64_t)t->rchunks + cap - 1) / cap;
+  t->rows_per_chunk *= factor;
+  t->rchunks = (uint32_t)((N + t->rows_per_chunk - 1) / t->rows_per_chunk);
+  t->items = batch * (int64_t)t->rchunks * t->ctiles;
 }
 
 }  // namespace kvq

@@ -122,10 +122,11 @@ kvq_status get_workspace(hipStream_t stream, Workspace* out) {
     return KVQ_OK;
   }
   void* p = nullptr;
-  KVQ_HIP(hipMalloc(&p, (size_t)kMaxPartials * (sizeof(double) + sizeof(float))));
+  KVQ_HIP(hipMalloc(&p, (size_t)kMaxPartials * (sizeof(double) + sizeof(float)) + (size_t)kColmaxFloats * sizeof(float)));
   Workspace w;
   w.sums = static_cast<double*>(p);
   w.maxes = reinterpret_cast<float*>(w.sums + kMaxPartials);
+  w.colmax = w.maxes + kMaxPartials;
   table[key] = w;
   *out = w;
   return KVQ_OK;

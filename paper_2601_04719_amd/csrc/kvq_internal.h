@@ -83,11 +83,14 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 // values / D int8 codes can be accessed with V-wide vectors, else 1.
 int pick_width(int64_t D, const void* fp32_ptr, const void* int8_ptr, int want);
 
-// Per-(device, stream) scratch for the partial results of the error kernels.
+// Per-(device, stream) scratch: partial results of the error kernels, and the per-row-chunk column
+// maxima of the scale reductions.
 constexpr int kMaxPartials = 8192;
+constexpr int64_t kColmaxFloats = (int64_t)1 << 22;  // 16 MiB
 struct Workspace {
   double* sums;   // [kMaxPartials]
   float* maxes;   // [kMaxPartials]
+  float* colmax;  // [kColmaxFloats]: [row chunk][batch * D]
 };
 kvq_status get_workspace(hipStream_t stream, Workspace* out);
 
@@ -95,6 +98,14 @@ kvq_status get_workspace(hipStream_t stream, Workspace* out);
 // scales = column absmax / qmax (127 for 8-bit codes, 7 for 4-bit codes)
 kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
                                 hipStream_t stream, float qmax = 127.0f);
+// second stage of a scale reduction that was split over row chunks:
+// scales[i] = max_r colmax[r * total + i] / qmax
+kvq_status launch_absmax_finalize(const float* colmax, float* scales, int64_t total, uint32_t rchunks, float qmax,
+                                  hipStream_t stream);
+// Row chunks a scale reduction over `total` = batch * D channels may use: bounded by the workspace.
+inline int64_t absmax_chunk_cap(int64_t total) { return total > 0 ? kColmaxFloats / total : 0; }
+// merges row chunks until at most `cap` (>= 1) remain
+void limit_row_chunks(Tiling* t, int64_t batch, int64_t N, int64_t cap);
 // 4-bit codes, two per byte (packed rows of D / 2 bytes); D is even.
 kvq_status launch_quantize_int4(const float* x, const float* scales, uint8_t* packed, int64_t batch, int64_t N,
                                 int64_t D, hipStream_t stream);

@@ -67,10 +67,10 @@ __device__ __forceinline__ uint32_t code_byte(float x, float div) {
 // ---- absmax --------------------------------------------------------------------------------
 // V = 8 (vector) or 1 (scalar); J column groups per lane, TX groups apart (see the fp32 kernel)
 template <typename T, int V, int J, int U>
-__global__ __launch_bounds__(kBlock) void absmax16_kernel(const uint16_t* __restrict__ x,
-                                                          uint32_t* __restrict__ max_bits, int64_t N, int64_t D,
-                                                          int tx_log2, uint32_t ctiles, uint32_t rchunks,
-                                                          int64_t rows_per_chunk, int64_t groups) {
+__global__ __launch_bounds__(kBlock) void absmax16_kernel(const uint16_t* __restrict__ x, float* __restrict__ dst,
+                                                          int64_t chunk_stride, int64_t N, int64_t D, int tx_log2,
+                                                          uint32_t ctiles, uint32_t rchunks, int64_t rows_per_chunk,
+                                                          int64_t groups) {
   __shared__ float red[J == 1 ? kBlock * V : 1];
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   const int TX = 1 << tx_log2;
@@ -130,27 +130,27 @@ __global__ __launch_bounds__(kBlock) void absmax16_kernel(const uint16_t* __rest
       }
     }
   }
+  // rchunks == 1: dst is the scale buffer and these are the final maxima; otherwise dst is the
+  // workspace, [row chunk][batch * D] with chunk_stride = batch * D, and a second kernel finishes
   if (it.ty == 0) {
+    const bool final_pass = rchunks == 1;
+    const uint32_t rc = (blockIdx.x / ctiles) % rchunks;
 #pragma unroll
     for (int j = 0; j < J; j++) {
       if (!act[j]) continue;
-      uint32_t* out = max_bits + it.slab * D + (group0 + (int64_t)j * TX) * V;
+      float* out = dst + (int64_t)rc * chunk_stride + it.slab * D + (group0 + (int64_t)j * TX) * V;
+      if (final_pass) {
 #pragma unroll
-      for (int i = 0; i < V; i++) {
-        const uint32_t bits = __float_as_uint(m[j][i]);
-        if (bits != 0u) atomicMax(out + i, bits);
+        for (int i = 0; i < V; i++) out[i] = m[j][i] / 127.0f;
+      } else if constexpr (V == 8) {
+        reinterpret_cast<f32x4*>(out)[0] = f32x4{m[j][0], m[j][1], m[j][2], m[j][3]};
+        reinterpret_cast<f32x4*>(out)[1] = f32x4{m[j][4], m[j][5], m[j][6], m[j][7]};
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; i++) out[i] = m[j][i];
       }
     }
   }
-}
-
-__global__ __launch_bounds__(kBlock) void fill_zero16(uint32_t* p, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n) p[i] = 0u;
-}
-__global__ __launch_bounds__(kBlock) void finalize16(float* scales, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n) scales[i] = scales[i] / 127.0f;
 }
 
 // ---- quantize --------------------------------------------------------------------------------
@@ -272,19 +272,18 @@ static kvq_status absmax16(const uint16_t* x, float* scales, int64_t batch, int6
                            hipStream_t stream) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  const Options& o = options();
   const int V = (D % 8 == 0 && aligned(x, 16)) ? 8 : 1;
   int J = 1;
   if (V == 8) {
     const int64_t groups = D / 8;
-    // wide workgroups only where every one of them still gets about 512 rows (as in the fp32 reduction)
-    const int64_t j_rows = batch * N * D / ((int64_t)dev.cus << 20);
-    while (J < 4 && J * 2 <= j_rows && (int64_t)kBlock * J < groups) J *= 2;
+    // as in the fp32 reduction: workgroups that span whole rows wherever rows are that wide
+    while (J < 4 && J < o.absmax_span && (int64_t)kBlock * J < groups) J *= 2;
   }
   constexpr int U1 = 8, UJ = 2;
   const int U = J == 1 ? U1 : UJ;
-  // narrow rows: four workgroups per compute unit hide the conversion work behind each other's loads;
-  // wide rows: one, because every extra row chunk costs a full row of atomics at the end
-  const int bpc = J == 1 ? 4 : 1;
+  // narrow rows: four workgroups per compute unit hide the conversion work behind each other's loads
+  const int bpc = (J == 1 ? 4 : 1) * o.absmax_blocks_per_cu;
   Tiling t = make_tiling(batch, N, D, V * J, U, (int64_t)dev.cus * bpc, kBlock, 0);
   if (J > 1) {
     t.tx_log2 = 8;
@@ -293,24 +292,25 @@ static kvq_status absmax16(const uint16_t* x, float* scales, int64_t batch, int6
     t.items = batch * (int64_t)t.rchunks * t.ctiles;
   }
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  const int64_t n_scales = batch * D;
-  const int64_t small = (n_scales + kBlock - 1) / kBlock;
-  if (small > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  uint32_t* bits = reinterpret_cast<uint32_t*>(scales);
-  hipLaunchKernelGGL(fill_zero16, dim3((uint32_t)small), dim3(kBlock), 0, stream, bits, n_scales);
-  KVQ_HIP(hipGetLastError());
+  const int64_t total = batch * D;
+  limit_row_chunks(&t, batch, N, absmax_chunk_cap(total));
+  float* dst = scales;
+  if (t.rchunks > 1) {
+    Workspace ws;
+    if (kvq_status s = get_workspace(stream, &ws)) return s;
+    dst = ws.colmax;
+  }
   const dim3 grid((uint32_t)t.items), block(kBlock);
-#define KVQ_AM16(V_, J_, U_)                                                                                   \
-  hipLaunchKernelGGL((absmax16_kernel<T, V_, J_, U_>), grid, block, 0, stream, x, bits, N, D, t.tx_log2, t.ctiles, \
-                     t.rchunks, t.rows_per_chunk, t.groups)
+#define KVQ_AM16(V_, J_, U_)                                                                                  \
+  hipLaunchKernelGGL((absmax16_kernel<T, V_, J_, U_>), grid, block, 0, stream, x, dst, total, N, D, t.tx_log2, \
+                     t.ctiles, t.rchunks, t.rows_per_chunk, t.groups)
   if (V == 1) KVQ_AM16(1, 1, U1);
   else if (J == 1) KVQ_AM16(8, 1, U1);
   else if (J == 2) KVQ_AM16(8, 2, UJ);
   else KVQ_AM16(8, 4, UJ);
 #undef KVQ_AM16
   KVQ_HIP(hipGetLastError());
-  hipLaunchKernelGGL(finalize16, dim3((uint32_t)small), dim3(kBlock), 0, stream, scales, n_scales);
-  KVQ_HIP(hipGetLastError());
+  if (t.rchunks > 1) return launch_absmax_finalize(dst, scales, total, t.rchunks, 127.0f, stream);
   return KVQ_OK;
 }
 

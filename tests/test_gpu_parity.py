@@ -487,6 +487,42 @@ def test_all_kernel_variants_give_identical_results():
             kvq.kvq_set_option(k, v)
 
 
+ABSMAX_KEYS = (kvq.OPT_ABSMAX_SPAN, kvq.OPT_ABSMAX_BLOCKS_PER_CU, kvq.OPT_ABSMAX_UNROLL)
+
+
+@pytest.mark.parametrize("shape", [(1, 3000, 8192), (3, 517, 2048), (1, 40000, 128), (700, 33, 64), (2, 9, 4100),
+                                   (1, 70, 1 << 20)],
+                         ids=lambda v: "x".join(map(str, v)))
+def test_scales_do_not_depend_on_how_rows_are_chunked(shape):
+    """The scale reduction splits a slab's rows over workgroups and merges their maxima through a workspace
+    of fixed size.  Lanes spanning 1..8 column groups, 1..16 workgroups per compute unit (one chunk per slab
+    up to hundreds; for the 2^20-channel matrix more chunks than the workspace holds, so they are merged
+    down) and every unroll must give the oracle's bits, for fp32 and for 16-bit inputs."""
+    batch, N, D = shape
+    rng = np.random.default_rng(N + D)
+    x = make_matrix(rng, batch, N, D)
+    s_ref = oracle.compute_scales(x)
+    x16 = x.astype(np.float16)
+    s16_ref = oracle.compute_scales(x16.astype(np.float32))
+    gx = torch.from_numpy(x.reshape(-1)).cuda()
+    gx16 = torch.from_numpy(x16.reshape(-1)).cuda()
+    scales = torch.empty(batch * D, dtype=torch.float32, device="cuda")
+    saved = [kvq.kvq_get_option(k) for k in ABSMAX_KEYS]
+    try:
+        for combo in itertools.product((1, 2, 8), (1, 4, 16), (4, 16)):
+            for k, v in zip(ABSMAX_KEYS, combo):
+                kvq.kvq_set_option(k, v)
+            scales.fill_(-1.0)
+            kvq.kvq_absmax_scales(gx, scales, batch, N, D)
+            assert_bits_equal(scales.cpu().numpy().reshape(s_ref.shape), s_ref, "fp32 scales %r" % (combo,))
+            scales.fill_(-1.0)
+            kvq.kvq_absmax_scales_t(kvq.DTYPE_F16, gx16, scales, batch, N, D)
+            assert_bits_equal(scales.cpu().numpy().reshape(s16_ref.shape), s16_ref, "fp16 scales %r" % (combo,))
+    finally:
+        for k, v in zip(ABSMAX_KEYS, saved):
+            kvq.kvq_set_option(k, v)
+
+
 # ------------------------------------------------------------------ numerics corner cases
 def test_ties_near_ties_and_clipping_with_given_scales():
     """Quotients on and next to .5 ties, scales that clip, tiny, huge, zero and negative scales."""
