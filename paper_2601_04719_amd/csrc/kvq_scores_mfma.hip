@@ -296,13 +296,24 @@ template <int G, int STEPS, int TU>
 kvq_status launch_g(const float* queries, const int8_t* codes, const float* scales, float* out, int64_t batch,
                     int64_t N, int64_t D, int64_t q_total, int64_t q_first, int q_count, int cus, size_t lds_bytes,
                     hipStream_t stream) {
-  // tokens per workgroup: whole passes of 4 waves x TU tiles, enough workgroups to fill the chip,
-  // few enough that the per-workgroup query preparation stays small against the codes it streams
+  // tokens per workgroup: whole passes of 4 waves x TU tiles.  Preparing the digits costs a workgroup
+  // time in proportion to queries x channels, so its walk grows with that: 256 G D/64 tokens for rows of
+  // 64-256 channels (swept 256..8192 tokens on [2048 x 4096 x 128], [4096 x 4096 x 64], [512 x 4096 x
+  // 256] at Q = 4, 8, 16: within 2 % of the best of each, up to 14 % better than one size for all), but
+  // no longer than leaves about 4 workgroups per compute unit.
   const int64_t pass = 4 * 16 * TU;
-  const int64_t want = (int64_t)cus * 16;
-  int64_t per = (batch * N + want - 1) / want;
-  per = (per + pass - 1) / pass * pass;
-  if (per < 512) per = 512;
+  int64_t per;
+  if (STEPS > 0) {
+    per = (int64_t)256 * G * STEPS;
+    const int64_t fill = (batch * N + (int64_t)cus * 4 - 1) / ((int64_t)cus * 4);
+    if (per > fill) per = fill;
+    per = (per + pass - 1) / pass * pass;
+  } else {
+    const int64_t want = (int64_t)cus * 16;
+    per = (batch * N + want - 1) / want;
+    per = (per + pass - 1) / pass * pass;
+    if (per < 512) per = 512;
+  }
   const int64_t chunks = (N + per - 1) / per;
   if (batch * chunks > INT32_MAX) return KVQ_ERR_OVERFLOW;
   const dim3 grid((uint32_t)(batch * chunks)), block(kBlock);
