@@ -612,6 +612,32 @@ def test_works_on_a_non_default_stream():
     assert float(g.sumsq.item()) == pytest.approx(ss_ref, rel=REL) and np.float32(g.maxabs.item()) == mx_ref
 
 
+def test_streams_do_not_share_scratch():
+    """The scale reduction and the error kernels keep partial results in a per-stream workspace.  Four
+    streams work on four different matrices at once, several rounds without synchronising in between;
+    every stream must end with its own matrix's oracle results."""
+    rng = np.random.default_rng(23)
+    shapes = [(1, 30000, 256), (4, 6000, 128), (1, 2500, 4096), (2, 9000, 512)]
+    xs = [(make_matrix(rng, *sh) * np.float32(10.0 ** i)).astype(np.float32) for i, sh in enumerate(shapes)]
+    gs = [Gpu(x) for x in xs]
+    streams = [torch.cuda.Stream() for _ in xs]
+    torch.cuda.synchronize()
+    for _ in range(5):
+        for g, st in zip(gs, streams):
+            h = st.cuda_stream
+            kvq.kvq_absmax_scales(g.x, g.scales, g.batch, g.N, g.D, stream=h)
+            kvq.kvq_quantize(g.x, g.scales, g.codes, g.batch, g.N, g.D, stream=h)
+            kvq.kvq_roundtrip_error(g.x, None, g.codes, g.scales, g.batch, g.N, g.D, g.sumsq, g.maxabs, stream=h)
+    torch.cuda.synchronize()
+    for x, g in zip(xs, gs):
+        s_ref = oracle.compute_scales(x)
+        q_ref = oracle.quantize(x, s_ref)
+        assert_bits_equal(g.scales.cpu().numpy().reshape(s_ref.shape), s_ref, "scales %r" % (g.shape,))
+        assert_bits_equal(g.codes.cpu().numpy().reshape(q_ref.shape), q_ref, "codes %r" % (g.shape,))
+        ss_ref, mx_ref = oracle.roundtrip_error(x, oracle.dequantize(q_ref, s_ref))
+        assert float(g.sumsq.item()) == pytest.approx(ss_ref, rel=REL) and np.float32(g.maxabs.item()) == mx_ref
+
+
 # ------------------------------------------------------------------ 4-bit codes
 def int4_round_trip(x, offset=0, given_scales=None):
     """kvq_*_int4 against the oracle's qmax = 7 functions: scales, packed bytes and x_hat bit-exact,
