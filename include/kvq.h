@@ -168,6 +168,17 @@ kvq_status kvq_append(const float *x_new, float *scales, float *scales_prev, int
                       kvq_stream_t stream);
 
 /*
+ * The same append for new tokens in a 16-bit format ("Memory Bottleneck in LLM Inference":
+ * activations and caches are kept in 16-bit formats): x_new [batch,m,D] holds fp16 or bf16
+ * values (dtype KVQ_DTYPE_F16 / KVQ_DTYPE_BF16, 2-byte aligned), which widen to fp32 exactly,
+ * so scales and codes are those kvq_append gives for the widened tokens.  KVQ_DTYPE_F32
+ * forwards to kvq_append; any other dtype is KVQ_ERR_ARG.  All other arguments as above.
+ */
+kvq_status kvq_append_t(int dtype, const void *x_new, float *scales, float *scales_prev, int8_t *codes,
+                        int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D,
+                        kvq_stream_t stream);
+
+/*
  * Scale computation and quantization in one call (same results as
  * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
  * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in

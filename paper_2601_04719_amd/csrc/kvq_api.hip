@@ -254,6 +254,19 @@ kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int
   return launch_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
 }
 
+kvq_status kvq_append_t(int dtype, const void* x_new, float* scales, float* scales_prev, int8_t* codes,
+                        int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D, kvq_stream_t stream) {
+  if (dtype == KVQ_DTYPE_F32)
+    return kvq_append(static_cast<const float*>(x_new), scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
+  if (dtype != KVQ_DTYPE_F16 && dtype != KVQ_DTYPE_BF16) return KVQ_ERR_ARG;
+  if (!x_new || !scales || !scales_prev || !codes) return KVQ_ERR_NULL;
+  if (n_old < 0 || m < 1) return KVQ_ERR_SHAPE;
+  if (kvq_status s = check_shape(batch, capacity, D)) return s;
+  if (m > capacity || n_old > capacity - m) return KVQ_ERR_ARG;
+  if (scales == scales_prev || !aligned(x_new, 2)) return KVQ_ERR_ARG;
+  return launch_append_16(dtype, x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
+}
+
 kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N,
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;

@@ -41,10 +41,31 @@ __device__ __forceinline__ uint32_t code_bits(float v, float s) {
 
 __device__ __forceinline__ float merged(float old, float cand) { return cand > old ? cand : old; }
 
+// new tokens come as fp32 (T = float) or as 16-bit patterns (T = f16_tag / bf16_tag), widened exactly
+template <typename T>
+struct Elem { typedef uint16_t type; };
+template <>
+struct Elem<float> { typedef float type; };
+template <typename T>
+__device__ __forceinline__ float load1(const typename Elem<T>::type* p) {
+  if constexpr (std::is_same<T, float>::value) return *p;
+  else return widen<T>(*p);
+}
+template <typename T>
+__device__ __forceinline__ f32x4 load4(const typename Elem<T>::type* p) {
+  if constexpr (std::is_same<T, float>::value) {
+    return *reinterpret_cast<const f32x4*>(p);
+  } else {
+    const u32x2 w = *reinterpret_cast<const u32x2*>(p);
+    return f32x4{widen<T>((uint16_t)(w.x & 0xffffu)), widen<T>((uint16_t)(w.x >> 16)),
+                 widen<T>((uint16_t)(w.y & 0xffffu)), widen<T>((uint16_t)(w.y >> 16))};
+  }
+}
+
 // ---- few new tokens: absmax of the new rows, merge, quantize the new rows ----
 // One lane per group of V channels of one slab; consecutive lanes own consecutive groups.
-template <int V>
-__global__ __launch_bounds__(kBlock) void append_small_kernel(const float* __restrict__ x_new,
+template <int V, typename T>
+__global__ __launch_bounds__(kBlock) void append_small_kernel(const typename Elem<T>::type* __restrict__ x_new,
                                                               float* __restrict__ scales,
                                                               float* __restrict__ scales_prev,
                                                               int8_t* __restrict__ codes, int64_t lanes,
@@ -54,17 +75,17 @@ __global__ __launch_bounds__(kBlock) void append_small_kernel(const float* __res
   if (id >= lanes) return;
   const int64_t slab = id / groups;
   const int64_t col = (id - slab * groups) * V;
-  const float* px = x_new + slab * m * D + col;
+  const typename Elem<T>::type* px = x_new + slab * m * D + col;
   float mx[V];
 #pragma unroll
   for (int i = 0; i < V; i++) mx[i] = 0.0f;
   for (int t = 0; t < m; t++) {
     if constexpr (V == 4) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(px + (int64_t)t * D);
+      const f32x4 v = load4<T>(px + (int64_t)t * D);
 #pragma unroll
       for (int i = 0; i < 4; i++) mx[i] = fmaxf(mx[i], fabsf(v[i]));
     } else {
-      mx[0] = fmaxf(mx[0], fabsf(px[(int64_t)t * D]));
+      mx[0] = fmaxf(mx[0], fabsf(load1<T>(px + (int64_t)t * D)));
     }
   }
   float nw[V];
@@ -91,12 +112,12 @@ __global__ __launch_bounds__(kBlock) void append_small_kernel(const float* __res
   int8_t* pc = codes + (slab * capacity + n_old) * D + col;
   for (int t = 0; t < m; t++) {
     if constexpr (V == 4) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(px + (int64_t)t * D);
+      const f32x4 v = load4<T>(px + (int64_t)t * D);
       const uint32_t w = code_bits(v.x, nw[0]) | (code_bits(v.y, nw[1]) << 8) | (code_bits(v.z, nw[2]) << 16) |
                          (code_bits(v.w, nw[3]) << 24);
       *reinterpret_cast<uint32_t*>(pc + (int64_t)t * D) = w;
     } else {
-      pc[(int64_t)t * D] = (int8_t)code_bits(px[(int64_t)t * D], nw[0]);
+      pc[(int64_t)t * D] = (int8_t)code_bits(load1<T>(px + (int64_t)t * D), nw[0]);
     }
   }
 }
@@ -174,12 +195,16 @@ __global__ __launch_bounds__(kBlock) void append_requant_kernel(int8_t* __restri
 
 }  // namespace
 
-kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
-                         int64_t n_old, int64_t m, int64_t capacity, int64_t D, hipStream_t stream) {
+// dtype: KVQ_DTYPE_F32 / F16 / BF16 -- the format of x_new
+template <typename T>
+static kvq_status append_t(int dtype, const typename Elem<T>::type* x_new, float* scales, float* scales_prev,
+                           int8_t* codes, int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D,
+                           hipStream_t stream) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
-  const bool wide = D % 4 == 0 && aligned(x_new, 16) && aligned(scales, 16) && aligned(scales_prev, 16) &&
-                    aligned(codes, 4);
+  // four channels per lane: one 16-byte (fp32) or 8-byte (16-bit) access to the new rows
+  const bool wide = D % 4 == 0 && aligned(x_new, 4 * sizeof(typename Elem<T>::type)) && aligned(scales, 16) &&
+                    aligned(scales_prev, 16) && aligned(codes, 4);
   const int V = wide ? 4 : 1;
   const int64_t groups = D / V;
 
@@ -189,14 +214,17 @@ kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, 
     const int64_t blocks = (lanes + kBlock - 1) / kBlock;
     if (blocks > INT32_MAX) return KVQ_ERR_OVERFLOW;
     if (wide)
-      hipLaunchKernelGGL(append_small_kernel<4>, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, x_new, scales,
+      hipLaunchKernelGGL((append_small_kernel<4, T>), dim3((uint32_t)blocks), dim3(kBlock), 0, stream, x_new, scales,
                          scales_prev, codes, lanes, groups, n_old, (int)m, capacity, D);
     else
-      hipLaunchKernelGGL(append_small_kernel<1>, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, x_new, scales,
+      hipLaunchKernelGGL((append_small_kernel<1, T>), dim3((uint32_t)blocks), dim3(kBlock), 0, stream, x_new, scales,
                          scales_prev, codes, lanes, groups, n_old, (int)m, capacity, D);
     KVQ_HIP(hipGetLastError());
   } else {
-    if (kvq_status s = launch_absmax_scales(x_new, scales_prev, batch, m, D, stream)) return s;
+    kvq_status s;
+    if constexpr (std::is_same<T, float>::value) s = launch_absmax_scales(x_new, scales_prev, batch, m, D, stream);
+    else s = launch_absmax_scales_16(dtype, x_new, scales_prev, batch, m, D, stream);
+    if (s != KVQ_OK) return s;
     const int64_t n = batch * D;
     const int64_t blocks = (n + kBlock - 1) / kBlock;
     if (blocks > INT32_MAX) return KVQ_ERR_OVERFLOW;
@@ -205,12 +233,14 @@ kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, 
   }
 
   // 2. cached rows of grown channels (rows [0, n_old) only: never the rows written by this call)
+  const bool wide_codes = D % 4 == 0 && aligned(scales, 16) && aligned(scales_prev, 16) && aligned(codes, 4);
   if (n_old > 0) {
     constexpr int U = 8;
-    Tiling t = make_tiling(batch, n_old, D, V, V == 4 ? U : 1, (int64_t)dev.cus * options().append_blocks_per_cu, kBlock, 0);
+    Tiling t = make_tiling(batch, n_old, D, wide_codes ? 4 : 1, wide_codes ? U : 1,
+                           (int64_t)dev.cus * options().append_blocks_per_cu, kBlock, 0);
     if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
     const dim3 grid((uint32_t)t.items), block(kBlock);
-    if (wide)
+    if (wide_codes)
       hipLaunchKernelGGL((append_requant_kernel<4, U>), grid, block, 0, stream, codes, scales, scales_prev, n_old,
                          capacity, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
     else
@@ -220,9 +250,28 @@ kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, 
   }
 
   // 3. the new rows
-  if (m > kSmallM)
-    return launch_quantize_strided(x_new, scales, codes + n_old * D, batch, m, D, m * D, capacity * D, stream);
+  if (m > kSmallM) {
+    if constexpr (std::is_same<T, float>::value)
+      return launch_quantize_strided(x_new, scales, codes + n_old * D, batch, m, D, m * D, capacity * D, stream);
+    else
+      return launch_quantize_16_strided(dtype, x_new, scales, codes + n_old * D, batch, m, D, m * D, capacity * D,
+                                        stream);
+  }
   return KVQ_OK;
+}
+
+kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
+                         int64_t n_old, int64_t m, int64_t capacity, int64_t D, hipStream_t stream) {
+  return append_t<float>(KVQ_DTYPE_F32, x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
+}
+
+kvq_status launch_append_16(int dtype, const void* x_new, float* scales, float* scales_prev, int8_t* codes,
+                            int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D,
+                            hipStream_t stream) {
+  const uint16_t* p = static_cast<const uint16_t*>(x_new);
+  return dtype == KVQ_DTYPE_F16
+             ? append_t<f16_tag>(dtype, p, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream)
+             : append_t<bf16_tag>(dtype, p, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
 }
 
 }  // namespace kvq

@@ -125,6 +125,10 @@ kvq_status launch_quantize_strided(const float* x, const float* scales, int8_t* 
 // channels, quantize the new tokens behind them.
 kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
                          int64_t n_old, int64_t m, int64_t capacity, int64_t D, hipStream_t stream);
+// the same with fp16 / bf16 new tokens (dtype: KVQ_DTYPE_F16 or KVQ_DTYPE_BF16)
+kvq_status launch_append_16(int dtype, const void* x_new, float* scales, float* scales_prev, int8_t* codes,
+                            int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D,
+                            hipStream_t stream);
 kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_hat, int64_t batch,
                              int64_t N, int64_t D, hipStream_t stream);
 // One-pass absmax + quantize for slabs that fit one workgroup's registers.
@@ -149,6 +153,9 @@ kvq_status launch_absmax_scales_16(int dtype, const void* x, float* scales, int6
                                    hipStream_t stream);
 kvq_status launch_quantize_16(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,
                               int64_t N, int64_t D, hipStream_t stream);
+// slab b of x starts x_slab elements after slab b-1, of codes c_slab (both multiples of D)
+kvq_status launch_quantize_16_strided(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,
+                                      int64_t N, int64_t D, int64_t x_slab, int64_t c_slab, hipStream_t stream);
 kvq_status launch_dequantize_16(int dtype, const int8_t* codes, const float* scales, void* x_hat, int64_t batch,
                                 int64_t N, int64_t D, hipStream_t stream);
 kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int64_t count, double* sumsq_out,
@@ -162,6 +169,43 @@ kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float*
 
 // ---- device helpers ----
 #ifdef __HIPCC__
+// 16-bit input formats: tags, and exact / round-to-nearest-even conversions on raw bit patterns
+struct f16_tag {};
+struct bf16_tag {};
+
+typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+
+// ---- element conversions -----------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float widen(uint16_t bits);
+template <>
+__device__ __forceinline__ float widen<f16_tag>(uint16_t bits) {
+  _Float16 h;
+  __builtin_memcpy(&h, &bits, 2);
+  return (float)h;
+}
+template <>
+__device__ __forceinline__ float widen<bf16_tag>(uint16_t bits) {
+  return __uint_as_float((uint32_t)bits << 16);
+}
+
+// round to nearest even (finite inputs)
+template <typename T>
+__device__ __forceinline__ uint16_t narrow(float v);
+template <>
+__device__ __forceinline__ uint16_t narrow<f16_tag>(float v) {
+  const _Float16 h = (_Float16)v;
+  uint16_t bits;
+  __builtin_memcpy(&bits, &h, 2);
+  return bits;
+}
+template <>
+__device__ __forceinline__ uint16_t narrow<bf16_tag>(float v) {
+  const uint32_t u = __float_as_uint(v);
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T* p) {
   if constexpr (NT) return __builtin_nontemporal_load(p);

@@ -13,42 +13,6 @@
 
 namespace kvq {
 
-struct f16_tag {};
-struct bf16_tag {};
-
-typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
-
-// ---- element conversions -----------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ float widen(uint16_t bits);
-template <>
-__device__ __forceinline__ float widen<f16_tag>(uint16_t bits) {
-  _Float16 h;
-  __builtin_memcpy(&h, &bits, 2);
-  return (float)h;
-}
-template <>
-__device__ __forceinline__ float widen<bf16_tag>(uint16_t bits) {
-  return __uint_as_float((uint32_t)bits << 16);
-}
-
-// round to nearest even (finite inputs)
-template <typename T>
-__device__ __forceinline__ uint16_t narrow(float v);
-template <>
-__device__ __forceinline__ uint16_t narrow<f16_tag>(float v) {
-  const _Float16 h = (_Float16)v;
-  uint16_t bits;
-  __builtin_memcpy(&bits, &h, 2);
-  return bits;
-}
-template <>
-__device__ __forceinline__ uint16_t narrow<bf16_tag>(float v) {
-  const uint32_t u = __float_as_uint(v);
-  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-
 template <typename T>
 __device__ __forceinline__ void widen8(const u16x8& raw, float (&out)[8]) {
 #pragma unroll
@@ -159,7 +123,8 @@ __global__ __launch_bounds__(kMaxBlock) void quantize16_kernel(const uint16_t* _
                                                                const float* __restrict__ scales,
                                                                int8_t* __restrict__ codes, int64_t N, int64_t D,
                                                                int tx_log2, uint32_t ctiles, uint32_t rchunks,
-                                                               int64_t rows_per_chunk, int64_t groups) {
+                                                               int64_t rows_per_chunk, int64_t groups,
+                                                               int64_t x_slab, int64_t c_slab) {
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * V;
@@ -177,8 +142,8 @@ __global__ __launch_bounds__(kMaxBlock) void quantize16_kernel(const uint16_t* _
   }
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
-  const uint16_t* px = x + (it.slab * N + row) * D + col;
-  int8_t* pc = codes + (it.slab * N + row) * D + col;
+  const uint16_t* px = x + it.slab * x_slab + row * D + col;  // slab pitches in elements
+  int8_t* pc = codes + it.slab * c_slab + row * D + col;
   if constexpr (V == 8) {
     auto do_rows = [&](auto tag) {
       constexpr int R = decltype(tag)::value;
@@ -316,16 +281,17 @@ static kvq_status absmax16(const uint16_t* x, float* scales, int64_t batch, int6
 
 template <typename T>
 static kvq_status quantize16(const uint16_t* x, const float* scales, int8_t* codes, int64_t batch, int64_t N,
-                             int64_t D, hipStream_t stream) {
+                             int64_t D, int64_t x_slab, int64_t c_slab, hipStream_t stream) {
+  // both slab pitches are multiples of D, so the alignment of row 0 of slab 0 decides for all rows
   const bool vec = D % 8 == 0 && aligned(x, 16) && aligned(codes, 8) && aligned(scales, 16);
   int U;
   Tiling t;
   if (kvq_status s = stream_tiling(batch, N, D, vec ? 8 : 1, vec, kQ16Unroll, kQ16Block, &U, &t, kQ16Passes)) return s;
   const dim3 grid((uint32_t)t.items), block(t.block);
-#define KVQ_Q16(U_) hipLaunchKernelGGL((quantize16_kernel<T, 8, U_>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups)
+#define KVQ_Q16(U_) hipLaunchKernelGGL((quantize16_kernel<T, 8, U_>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, x_slab, c_slab)
   if (!vec)
     hipLaunchKernelGGL((quantize16_kernel<T, 1, 1>), grid, block, 0, stream, x, scales, codes, N, D, t.tx_log2,
-                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
+                       t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, x_slab, c_slab);
   else if (U == 1) KVQ_Q16(1);
   else if (U == 2) KVQ_Q16(2);
   else KVQ_Q16(4);
@@ -362,9 +328,13 @@ kvq_status launch_absmax_scales_16(int dtype, const void* x, float* scales, int6
 }
 kvq_status launch_quantize_16(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,
                               int64_t N, int64_t D, hipStream_t stream) {
+  return launch_quantize_16_strided(dtype, x, scales, codes, batch, N, D, N * D, N * D, stream);
+}
+kvq_status launch_quantize_16_strided(int dtype, const void* x, const float* scales, int8_t* codes, int64_t batch,
+                                      int64_t N, int64_t D, int64_t x_slab, int64_t c_slab, hipStream_t stream) {
   const uint16_t* p = static_cast<const uint16_t*>(x);
-  return dtype == KVQ_DTYPE_F16 ? quantize16<f16_tag>(p, scales, codes, batch, N, D, stream)
-                                : quantize16<bf16_tag>(p, scales, codes, batch, N, D, stream);
+  return dtype == KVQ_DTYPE_F16 ? quantize16<f16_tag>(p, scales, codes, batch, N, D, x_slab, c_slab, stream)
+                                : quantize16<bf16_tag>(p, scales, codes, batch, N, D, x_slab, c_slab, stream);
 }
 kvq_status launch_dequantize_16(int dtype, const int8_t* codes, const float* scales, void* x_hat, int64_t batch,
                                 int64_t N, int64_t D, hipStream_t stream) {

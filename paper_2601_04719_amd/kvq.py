@@ -23,7 +23,7 @@ OPT_APPEND_BLOCKS_PER_CU = 12
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
-    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
@@ -71,6 +71,8 @@ def lib():
             getattr(L, name).restype = i32
         L.kvq_append.argtypes = [p, p, p, p, i64, i64, i64, i64, i64, p]
         L.kvq_append.restype = i32
+        L.kvq_append_t.argtypes = [i32, p, p, p, p, i64, i64, i64, i64, i64, p]
+        L.kvq_append_t.restype = i32
         L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.restype = i32
         L.kvq_scores_from_codes.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
@@ -190,6 +192,11 @@ def kvq_dequantize_fp8(codes, scales, x_hat, batch, N, D, stream=None):
 def kvq_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):
     _check(lib().kvq_append(_addr(x_new), _addr(scales), _addr(scales_prev), _addr(codes), batch, n_old, m,
                             capacity, D, _stream(stream)), "kvq_append")
+
+
+def kvq_append_t(dtype, x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):
+    _check(lib().kvq_append_t(dtype, _addr(x_new), _addr(scales), _addr(scales_prev), _addr(codes), batch, n_old, m,
+                              capacity, D, _stream(stream)), "kvq_append_t")
 
 
 VARIANT_PRODUCTION, VARIANT_NAIVE, VARIANT_TILED, VARIANT_COARSENED, VARIANT_VECTORIZED = 0, 1, 2, 3, 4

@@ -109,11 +109,14 @@ def main():
         return
 
     if args.append:
-        print("| cache batch x capacity x D | new tokens m | slabs (batch > 1) or channels (batch = 1) that grow | "
-              "channels grown | mean ms | min ms |")
-        print("|---|---|---|---|---|---|")
-        for (B, cap, D, m) in [(2048, 4096, 128, 1), (256, 4096, 128, 1), (32, 131072, 128, 1), (1, 131072, 8192, 1),
-                               (2048, 4096, 128, 16), (2048, 4096, 128, 512), (1, 131072, 8192, 1024)]:
+        print("| cache batch x capacity x D | new tokens m | token format | slabs (batch > 1) or channels (batch = 1) "
+              "that grow | channels grown | mean ms | min ms |")
+        print("|---|---|---|---|---|---|---|")
+        for (B, cap, D, m, fmt) in [(2048, 4096, 128, 1, "fp32"), (256, 4096, 128, 1, "fp32"),
+                                    (32, 131072, 128, 1, "fp32"), (1, 131072, 8192, 1, "fp32"),
+                                    (2048, 4096, 128, 16, "fp32"), (2048, 4096, 128, 512, "fp32"),
+                                    (1, 131072, 8192, 1024, "fp32"), (2048, 4096, 128, 1, "bf16"),
+                                    (2048, 4096, 128, 512, "bf16"), (1, 131072, 8192, 1024, "bf16")]:
             n_old = cap - m
             codes = torch.randint(-127, 128, (B * cap * D,), dtype=torch.int8, device="cuda")
             scales0 = torch.rand(B * D, device="cuda") + 1.0
@@ -129,17 +132,22 @@ def main():
                     else:
                         x[:, :, :max(1, int(frac * D))] *= 4
                 x = x.contiguous()
+                if fmt == "bf16":
+                    x = x.to(torch.bfloat16)
 
                 def step():
                     scales.copy_(scales0)          # every timed call starts from the same cache state
-                    kvq.kvq_append(x, scales, prev, codes, B, n_old, m, cap, D)
+                    if fmt == "bf16":
+                        kvq.kvq_append_t(kvq.DTYPE_BF16, x, scales, prev, codes, B, n_old, m, cap, D)
+                    else:
+                        kvq.kvq_append(x, scales, prev, codes, B, n_old, m, cap, D)
 
                 mean, mn = timeit(step)
                 tc, _ = timeit(lambda: scales.copy_(scales0))
                 step()
                 grown = int((scales > scales0).sum().item())
-                print("| %d x %d x %d | %d | %.0f %% | %d | %.4f | %.4f |" % (B, cap, D, m, 100 * frac, grown,
-                                                                           mean - tc, mn - tc))
+                print("| %d x %d x %d | %d | %s | %.0f %% | %d | %.4f | %.4f |" % (B, cap, D, m, fmt, 100 * frac, grown,
+                                                                                mean - tc, mn - tc))
                 sys.stdout.flush()
             del codes
             torch.cuda.empty_cache()

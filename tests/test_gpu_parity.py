@@ -861,6 +861,54 @@ def test_streaming_append_decode_step_on_a_full_size_cache():
     assert grew[3, 5] and grew[200].all() and grew.sum() < 0.2 * grew.size
 
 
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+@pytest.mark.parametrize("shape,chunks", [((3, 300, 128), (17, 1, 100, 1, 1, 64, 116)), ((2, 40, 20), (1, 16, 1, 22)),
+                                          ((1, 33, 3), (1, 1, 31)), ((4, 2100, 256), (2048, 1, 1, 50)),
+                                          ((1, 9, 4100), (1, 3, 5)), ((2, 50, 65), (20, 1, 29))],
+                         ids=lambda v: "x".join(map(str, v)))
+@pytest.mark.parametrize("offset", [0, 1])
+def test_streaming_append_of_sixteen_bit_tokens(shape, chunks, offset, fmt):
+    """kvq_append_t: new tokens arrive as fp16 / bf16; the cache must be what the oracle's append gives
+    for the widened tokens, bit for bit, through decode steps, prefill chunks and misaligned buffers."""
+    batch, cap, D = shape
+    rng = np.random.default_rng(hash((shape, offset, fmt)) % (1 << 31))
+    N = sum(chunks)
+    x16 = oracle.narrow16(np.clip(growing_tokens(rng, batch, N, D), -60000, 60000), fmt)
+    xw = oracle.widen16(x16, fmt)
+    dt = kvq.DTYPE_F16 if fmt == "f16" else kvq.DTYPE_BF16
+    g = GpuCache(batch, cap, D, offset)
+    ref_codes = np.full((batch, cap, D), 55, dtype=np.int8)
+    ref_scales = np.zeros((batch, D), dtype=np.float32)
+    n, grown_total = 0, 0
+    for m in chunks:
+        tok = np.ascontiguousarray(x16[:, n:n + m])
+        buf = torch.zeros(tok.size + 64, dtype=torch.int16, device="cuda")
+        xs = buf[offset:offset + tok.size]
+        xs.copy_(torch.from_numpy(tok.view(np.int16).reshape(-1)))
+        kvq.kvq_append_t(dt, xs, g.scales, g.prev, g.codes, batch, n, m, cap, D)
+        ref_codes, new_scales, ref_prev = oracle.append(ref_codes, ref_scales, n, np.ascontiguousarray(xw[:, n:n + m]))
+        grown_total += int(((new_scales > ref_scales) & (n > 0)).sum())
+        ref_scales, n = new_scales, n + m
+        codes, scales, prev = g.state()
+        assert_bits_equal(scales, ref_scales, "scales after %d tokens" % n)
+        assert_bits_equal(prev, ref_prev, "previous scales after %d tokens" % n)
+        assert_bits_equal(codes, ref_codes, "cache after %d tokens" % n)
+    assert g.guards_intact()
+    assert grown_total > 0
+    # fp32 through the typed entry point is the fp32 call
+    g32 = GpuCache(batch, cap, D, offset)
+    buf = torch.zeros(xw[:, :chunks[0]].size + 64, dtype=torch.float32, device="cuda")
+    xs = buf[offset:offset + xw[:, :chunks[0]].size]
+    xs.copy_(torch.from_numpy(np.ascontiguousarray(xw[:, :chunks[0]]).reshape(-1)))
+    kvq.kvq_append_t(kvq.DTYPE_F32, xs, g32.scales, g32.prev, g32.codes, batch, 0, chunks[0], cap, D)
+    want, _, _ = oracle.append(np.full((batch, cap, D), 55, dtype=np.int8), np.zeros((batch, D), np.float32), 0,
+                               np.ascontiguousarray(xw[:, :chunks[0]]))
+    assert_bits_equal(g32.state()[0], want, "fp32 through kvq_append_t")
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.kvq_append_t(9, xs, g32.scales, g32.prev, g32.codes, batch, 0, 1, cap, D)
+    assert e.value.status == kvq.ERR_ARG
+
+
 def test_streaming_append_argument_errors():
     g = GpuCache(1, 8, 4)
     x = torch.zeros(4 * 4, dtype=torch.float32, device="cuda")
