@@ -339,6 +339,30 @@ int kvq_last_hip_error(void);
 #define KVQ_OPT_ABSMAX_SPAN 10
 #define KVQ_OPT_ABSMAX_BLOCKS_PER_CU 11
 #define KVQ_OPT_APPEND_BLOCKS_PER_CU 12
+/*
+ * The launch plan of a streaming call for a shape, computed on the host without touching a
+ * device: how scale reduction, quantize or dequantize (fp32 matrices, current options) would
+ * cut [batch,N,D] into workgroups on a GPU with `compute_units` units.  For tests of the host
+ * logic and for tuning; nothing is launched.
+ *   vector_access  nonzero: buffers are taken to be 16-byte aligned (the vector kernels where D
+ *                  allows); zero: the scalar kernels
+ *   plan_out       HOST pointer to 8 values, written:
+ *     [0] V  adjacent channels a lane owns per column group   [1] J  column groups per lane, TX groups
+ *     [2] threads per workgroup = TX * TY                           apart (1 except in the reduction)
+ *     [3] TX lanes along a row; lane tx of column tile c owns groups (c*J + j)*TX + tx, j < J
+ *     [4] column tiles per row   [5] row chunks per slab   [6] rows per chunk (the last may be short)
+ *     [7] rows a lane keeps in flight
+ *   work items = batch * row chunks * column tiles; item i is column tile i % tiles of row chunk
+ *   (i / tiles) % chunks of slab i / (tiles * chunks); lane ty of a workgroup visits rows
+ *   r0 + ty, r0 + ty + TY, ... of its chunk.
+ * KVQ_ERR_ARG for an unknown call or compute_units outside 1..65536; shape errors as elsewhere.
+ */
+#define KVQ_PLAN_ABSMAX 0
+#define KVQ_PLAN_QUANTIZE 1
+#define KVQ_PLAN_DEQUANTIZE 2
+kvq_status kvq_plan(int call, int64_t batch, int64_t N, int64_t D, int vector_access, int compute_units,
+                    int64_t *plan_out);
+
 kvq_status kvq_set_option(int key, int value);
 int kvq_get_option(int key);
 

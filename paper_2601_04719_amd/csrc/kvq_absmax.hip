@@ -173,12 +173,9 @@ static kvq_status launch_absmax_t(const float* x, float* dst, int64_t chunk_stri
   return KVQ_OK;
 }
 
-kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
-                                hipStream_t stream, float qmax) {
-  const DeviceInfo dev = current_device();
-  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, int* J_out, int* U_out, Tiling* t_out) {
   const Options& o = options();
-  const int V = (D % 4 == 0 && aligned(x, 16)) ? 4 : 1;
+  const int V = vec ? 4 : 1;
   // J column groups per lane: as many as it takes for a workgroup to span whole rows, at most 8.
   // Measured on D = 8192 (J = 1 / 4 / 8, one workgroup per compute unit): 4096 rows 37 / 30 / 35 us,
   // 16384 rows 85.6 / 84.6 / 86.4 us, 65536 rows 337 / 312 / 313 us, 131072 rows 700 / 663 / 610 us:
@@ -187,7 +184,7 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   if (V == 4) {
     const int64_t groups = D / 4;
     const int64_t elements = batch * N * D;
-    const int jmax = elements >= ((int64_t)dev.cus << 22) ? 8 : 4;
+    const int jmax = elements >= ((int64_t)cus << 22) ? 8 : 4;
     while (J < o.absmax_span && J < jmax && (int64_t)kBlock * J < groups) J *= 2;
   }
   // rows in flight: J * U 16-byte loads per lane, at most 16
@@ -196,12 +193,11 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   if (J >= 2 && U > 4) U = 4;
   int passes = o.absmax_passes;
   // tiling in units of J * V channels per lane
-  Tiling t = make_tiling(batch, N, D, V * J, U, (int64_t)dev.cus * o.absmax_blocks_per_cu, kBlock, passes);
+  Tiling t = make_tiling(batch, N, D, V * J, U, (int64_t)cus * o.absmax_blocks_per_cu, kBlock, passes);
   while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
     passes *= 2;
-    t = make_tiling(batch, N, D, V * J, U, (int64_t)dev.cus * o.absmax_blocks_per_cu, kBlock, passes);
+    t = make_tiling(batch, N, D, V * J, U, (int64_t)cus * o.absmax_blocks_per_cu, kBlock, passes);
   }
-  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   if (J > 1) {
     // make_tiling sized TX for D / (V*J) lane-columns; with J > 1 rows are at least a workgroup wide
     t.tx_log2 = 8;
@@ -209,8 +205,24 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
     t.ctiles = (uint32_t)((t.groups + (int64_t)kBlock * J - 1) / ((int64_t)kBlock * J));
     t.items = batch * (int64_t)t.rchunks * t.ctiles;
   }
+  limit_row_chunks(&t, batch, N, absmax_chunk_cap(batch * D));
+  if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  *J_out = J;
+  *U_out = U;
+  *t_out = t;
+  return KVQ_OK;
+}
+
+kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                hipStream_t stream, float qmax) {
+  const DeviceInfo dev = current_device();
+  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  const Options& o = options();
+  const int V = (D % 4 == 0 && aligned(x, 16)) ? 4 : 1;
+  int J, U;
+  Tiling t;
+  if (kvq_status s = absmax_plan(dev.cus, batch, N, D, V == 4, &J, &U, &t)) return s;
   const int64_t total = batch * D;
-  limit_row_chunks(&t, batch, N, absmax_chunk_cap(total));
   float* dst = scales;
   if (t.rchunks > 1) {
     Workspace ws;

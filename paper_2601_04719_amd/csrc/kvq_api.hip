@@ -90,6 +90,12 @@ kvq_status stream_tiling(int64_t batch, int64_t N, int64_t D, int V, bool vector
                          int default_block, int* U_out, Tiling* t_out, int default_passes) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  return stream_tiling_for(dev.cus, batch, N, D, V, vector_lanes, default_unroll, default_block, U_out, t_out,
+                           default_passes);
+}
+
+kvq_status stream_tiling_for(int cus, int64_t batch, int64_t N, int64_t D, int V, bool vector_lanes,
+                             int default_unroll, int default_block, int* U_out, Tiling* t_out, int default_passes) {
   const Options o = options();
   int U = o.codec_unroll > 0 ? o.codec_unroll : default_unroll;
   if (!vector_lanes) U = 1;
@@ -97,11 +103,11 @@ kvq_status stream_tiling(int64_t batch, int64_t N, int64_t D, int V, bool vector
   // the passes option, when moved off its default of 1, overrides a kernel's own default
   int passes = o.passes_per_block != 1 ? o.passes_per_block : default_passes;
   const int block = o.block_threads > 0 ? o.block_threads : default_block;
-  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
+  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)cus * o.blocks_per_cu, block, passes);
   // one-shot workgroups by default; fall back to longer walks only when the grid would not be indexable
   while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
     passes *= 2;
-    t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * o.blocks_per_cu, block, passes);
+    t = make_tiling(batch, N, D, V, U, (int64_t)cus * o.blocks_per_cu, block, passes);
   }
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   *U_out = U;
@@ -252,6 +258,36 @@ kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int
   if (m > capacity || n_old > capacity - m) return KVQ_ERR_ARG;
   if (scales == scales_prev) return KVQ_ERR_ARG;
   return launch_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
+}
+
+kvq_status kvq_plan(int call, int64_t batch, int64_t N, int64_t D, int vector_access, int compute_units,
+                    int64_t* plan_out) {
+  if (!plan_out) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  if (compute_units < 1 || compute_units > 65536) return KVQ_ERR_ARG;
+  int J = 1, U = 1;
+  Tiling t;
+  if (call == KVQ_PLAN_ABSMAX) {
+    if (kvq_status s = absmax_plan(compute_units, batch, N, D, vector_access && D % 4 == 0, &J, &U, &t)) return s;
+    t.V /= J;
+  } else if (call == KVQ_PLAN_QUANTIZE || call == KVQ_PLAN_DEQUANTIZE) {
+    const int V = vector_access ? pick_width(D, nullptr, nullptr, options().codec_width) : 1;
+    const bool q = call == KVQ_PLAN_QUANTIZE;
+    if (kvq_status s = stream_tiling_for(compute_units, batch, N, D, V, V > 1, q ? kQuantUnroll : kDequantUnroll,
+                                         q ? kQuantBlock : kDequantBlock, &U, &t))
+      return s;
+  } else {
+    return KVQ_ERR_ARG;
+  }
+  plan_out[0] = t.V;
+  plan_out[1] = J;
+  plan_out[2] = t.block;
+  plan_out[3] = (int64_t)1 << t.tx_log2;
+  plan_out[4] = t.ctiles;
+  plan_out[5] = t.rchunks;
+  plan_out[6] = t.rows_per_chunk;
+  plan_out[7] = U;
+  return KVQ_OK;
 }
 
 kvq_status kvq_append_t(int dtype, const void* x_new, float* scales, float* scales_prev, int8_t* codes,

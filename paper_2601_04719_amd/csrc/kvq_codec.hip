@@ -264,7 +264,7 @@ kvq_status launch_quantize_strided(const float* x, const float* scales, int8_t* 
   int U;
   Tiling t;
   // both slab pitches are multiples of D, so the alignment of row 0 of slab 0 decides for all rows
-  if (kvq_status s = codec_tiling(batch, N, D, x, codes, scales, 4, 512, &U, &t)) return s;
+  if (kvq_status s = codec_tiling(batch, N, D, x, codes, scales, kQuantUnroll, kQuantBlock, &U, &t)) return s;
   const bool nt = options().nontemporal != 0;
   return dispatch_vu(t.V, U, [&](auto v, auto u) {
     return launch_q<decltype(v)::value, decltype(u)::value>(x, scales, codes, N, D, t, nt, stream, x_slab, c_slab);
@@ -275,7 +275,7 @@ kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_
                              int64_t N, int64_t D, hipStream_t stream) {
   int U;
   Tiling t;
-  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, 2, 256, &U, &t)) return s;
+  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, kDequantUnroll, kDequantBlock, &U, &t)) return s;
   const bool nt = options().nontemporal != 0;
   return dispatch_vu(t.V, U, [&](auto v, auto u) {
     return launch_d<decltype(v)::value, decltype(u)::value>(codes, scales, x_hat, N, D, t, nt, stream);

@@ -46,6 +46,16 @@ Tiling make_tiling(int64_t batch, int64_t N, int64_t D, int V, int unroll, int64
 // say otherwise, one-shot workgroups.  vector_lanes = false is the scalar fallback (one row at a time).
 kvq_status stream_tiling(int64_t batch, int64_t N, int64_t D, int V, bool vector_lanes, int default_unroll,
                          int default_block, int* U_out, Tiling* t_out, int default_passes = 1);
+// the same for a given number of compute units (host arithmetic only, no device needed)
+kvq_status stream_tiling_for(int cus, int64_t batch, int64_t N, int64_t D, int V, bool vector_lanes,
+                             int default_unroll, int default_block, int* U_out, Tiling* t_out,
+                             int default_passes = 1);
+// Launch shape of the fp32 scale reduction: J column groups per lane, U rows in flight, tiling in units of
+// J * V channels per lane, row chunks limited to what the workspace holds.  vec = 16-byte row access.
+kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, int* J_out, int* U_out, Tiling* t_out);
+
+// default launch shapes of the fp32 codec kernels: rows in flight per lane, threads per workgroup
+constexpr int kQuantUnroll = 4, kQuantBlock = 512, kDequantUnroll = 2, kDequantBlock = 256;
 
 struct Options {
   int codec_width = 4;

@@ -23,7 +23,7 @@ OPT_APPEND_BLOCKS_PER_CU = 12
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
-    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_plan",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
@@ -73,6 +73,8 @@ def lib():
         L.kvq_append.restype = i32
         L.kvq_append_t.argtypes = [i32, p, p, p, p, i64, i64, i64, i64, i64, p]
         L.kvq_append_t.restype = i32
+        L.kvq_plan.argtypes = [i32, i64, i64, i64, i32, i32, p]
+        L.kvq_plan.restype = i32
         L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.restype = i32
         L.kvq_scores_from_codes.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
@@ -197,6 +199,18 @@ def kvq_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, 
 def kvq_append_t(dtype, x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):
     _check(lib().kvq_append_t(dtype, _addr(x_new), _addr(scales), _addr(scales_prev), _addr(codes), batch, n_old, m,
                               capacity, D, _stream(stream)), "kvq_append_t")
+
+
+PLAN_ABSMAX, PLAN_QUANTIZE, PLAN_DEQUANTIZE = 0, 1, 2
+PLAN_FIELDS = ("V", "J", "block", "TX", "ctiles", "rchunks", "rows_per_chunk", "unroll")
+
+
+def kvq_plan(call, batch, N, D, vector_access=True, compute_units=256):
+    """Host-side launch plan as a dict (see include/kvq.h); no device is touched."""
+    out = (ctypes.c_int64 * 8)()
+    _check(lib().kvq_plan(call, batch, N, D, int(bool(vector_access)), compute_units,
+                          ctypes.cast(out, ctypes.c_void_p)), "kvq_plan")
+    return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
 
 VARIANT_PRODUCTION, VARIANT_NAIVE, VARIANT_TILED, VARIANT_COARSENED, VARIANT_VECTORIZED = 0, 1, 2, 3, 4

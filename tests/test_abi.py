@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2601_04719_amd import kvq
@@ -98,3 +99,80 @@ def test_oracle_and_product_share_no_code():
         if f.endswith((".py", ".c", ".h")):
             src = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2601_04719_amd" not in src and "libkvq.so" not in src and "hip/" not in src, f
+
+
+# ------------------------------------------------------------------ host logic: launch plans
+def _coverage(plan, batch, N, D):
+    """How often each element is visited when every work item of a plan is decoded as the header
+    documents (item -> column tile, row chunk, slab; lane (tx, ty) -> column groups and rows)."""
+    V, J, block, TX = plan["V"], plan["J"], plan["block"], plan["TX"]
+    ctiles, rchunks, rpc = plan["ctiles"], plan["rchunks"], plan["rows_per_chunk"]
+    TY = block // TX
+    assert TX * TY == block and TY >= 1
+    seen = np.zeros((batch, N, D), dtype=np.int32)
+    for item in range(batch * rchunks * ctiles):
+        ct, rest = item % ctiles, item // ctiles
+        rc, slab = rest % rchunks, rest // rchunks
+        r0, r1 = rc * rpc, min(rc * rpc + rpc, N)
+        assert r0 < N, "empty row chunk"
+        rows = np.zeros(N, dtype=np.int32)
+        for ty in range(TY):
+            rows[r0 + ty:r1:TY] += 1
+        cols = np.zeros(D + V, dtype=np.int32)
+        c0 = (((ct * J + np.arange(J))[:, None] * TX + np.arange(TX)[None, :]) * V).reshape(-1)
+        c0 = c0[c0 < D]
+        for v in range(V):
+            np.add.at(cols, c0 + v, 1)
+        cols = cols[:D]
+        seen[slab, r0:r1] += rows[r0:r1, None] * cols[None, :]
+    return seen
+
+
+def test_launch_plans_visit_every_element_exactly_once():
+    """The host side decides lane width, workgroup shape, column tiles and row chunks.  Whatever it
+    decides, decoding all work items must touch every (slab, row, channel) exactly once -- checked by
+    enumeration on small matrices, for several compute-unit counts, vector and scalar kernels, and the
+    launch-shape options a caller may set."""
+    rng = np.random.default_rng(11)
+    shapes = [(1, 1, 1), (1, 7, 3), (2, 33, 20), (1, 300, 64), (3, 65, 128), (1, 40, 1028), (2, 19, 2048),
+              (1, 9, 4100), (1, 130, 8192), (5, 1, 256), (1, 1000, 8)]
+    shapes += [(int(rng.integers(1, 4)), int(rng.integers(1, 200)), int(rng.integers(1, 600))) for _ in range(12)]
+    keys = (kvq.OPT_CODEC_WIDTH, kvq.OPT_CODEC_UNROLL, kvq.OPT_BLOCKS_PER_CU, kvq.OPT_BLOCK_THREADS,
+            kvq.OPT_PASSES_PER_BLOCK, kvq.OPT_ABSMAX_UNROLL, kvq.OPT_ABSMAX_PASSES, kvq.OPT_ABSMAX_SPAN,
+            kvq.OPT_ABSMAX_BLOCKS_PER_CU)
+    saved = [kvq.kvq_get_option(k) for k in keys]
+    settings = [saved, [16, 8, 1, 64, 3, 16, 0, 8, 64], [8, 1, 64, 128, 1, 4, 2, 2, 7]]
+    try:
+        for setting in settings:
+            for k, v in zip(keys, setting):
+                kvq.kvq_set_option(k, v)
+            for (batch, N, D) in shapes:
+                for call in (kvq.PLAN_ABSMAX, kvq.PLAN_QUANTIZE, kvq.PLAN_DEQUANTIZE):
+                    for vec, cus in (((True, 256), (False, 256), (True, 1), (True, 5000)) if setting is saved
+                                     else ((True, 256), (False, 104))):
+                        plan = kvq.kvq_plan(call, batch, N, D, vec, cus)
+                        seen = _coverage(plan, batch, N, D)
+                        assert (seen == 1).all(), (setting, call, (batch, N, D), vec, cus, plan)
+    finally:
+        for k, v in zip(keys, saved):
+            kvq.kvq_set_option(k, v)
+
+
+def test_launch_plans_of_the_benchmark_shapes():
+    """Full-size shapes, by arithmetic: rows and columns are covered without an empty chunk or tile, the
+    grid can be indexed, vector lanes are used, and a reduction split over row chunks fits its workspace."""
+    for (batch, N, D) in [(1, 1024, 64), (1, 32768, 128), (256, 4096, 128), (1, 16384, 8192), (1, 131072, 8192),
+                          (2048, 4096, 128), (1, 1 << 21, 512), (65536, 64, 128), (1, 16, 1 << 22)]:
+        for call in (kvq.PLAN_ABSMAX, kvq.PLAN_QUANTIZE, kvq.PLAN_DEQUANTIZE):
+            p = kvq.kvq_plan(call, batch, N, D, True, 256)
+            assert p["V"] == 4 and p["block"] % p["TX"] == 0
+            assert (p["rchunks"] - 1) * p["rows_per_chunk"] < N <= p["rchunks"] * p["rows_per_chunk"]
+            span = p["TX"] * p["V"] * p["J"]
+            assert (p["ctiles"] - 1) * span < D <= p["ctiles"] * span
+            assert batch * p["rchunks"] * p["ctiles"] < 2 ** 31
+            if call == kvq.PLAN_ABSMAX and p["rchunks"] > 1:
+                assert p["rchunks"] * batch * D <= 1 << 22
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_plan(7, 1, 8, 8)
+    with pytest.raises(kvq.KvqError):
+        kvq.kvq_plan(kvq.PLAN_QUANTIZE, 1, 8, 8, True, 0)
