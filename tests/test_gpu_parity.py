@@ -584,12 +584,17 @@ def test_results_are_deterministic_run_to_run():
         assert g.attn_score_error(W.queries(2), False) == first[4]
 
 
-def test_scales_buffer_is_reset_on_stream_before_the_reduction():
-    """The scale buffer doubles as the reduction scratch: stale larger values must not survive."""
-    x = W.generate(1)[0]
-    g = Gpu(x)
-    g.scales.fill_(1e30)
-    assert_bits_equal(g.absmax_scales()[0], oracle.compute_scales(x), "scales after stale contents")
+def test_stale_contents_of_the_scale_buffer_and_workspace_do_not_survive():
+    """Whatever the scale buffer held, and whatever an earlier, larger reduction left in the workspace of
+    per-chunk maxima, the scales are those of the matrix at hand."""
+    big = make_matrix(np.random.default_rng(3), 1, 40000, 128) * np.float32(1e6)   # many row chunks, huge maxima
+    gb = Gpu(big)
+    assert_bits_equal(gb.absmax_scales(), oracle.compute_scales(big), "large matrix first")
+    for cfg in (1, 2):
+        x = W.generate(cfg)[0]
+        g = Gpu(x)
+        g.scales.fill_(1e30)
+        assert_bits_equal(g.absmax_scales()[0], oracle.compute_scales(x), "scales after stale contents")
 
 
 def test_works_on_a_non_default_stream():
