@@ -312,7 +312,8 @@ int kvq_last_hip_error(void);
  *   KVQ_OPT_CODEC_WIDTH     elements per lane in quantize/dequantize: 4, 8 or 16
  *   KVQ_OPT_CODEC_UNROLL    rows in flight per lane: 1, 2, 4 or 8; 0 = each kernel's default
  *   KVQ_OPT_BLOCKS_PER_CU   target workgroups per compute unit (used by the error reductions,
- *                           and by quantize/dequantize when PASSES_PER_BLOCK is 0): 1..64
+ *                           and by quantize/dequantize when PASSES_PER_BLOCK is 0): 1..64;
+ *                           0 = each kernel's default
  *   KVQ_OPT_NONTEMPORAL     0/1: streaming cache hints on loads and stores
  *   KVQ_OPT_BLOCK_THREADS   workgroup size of quantize/dequantize: 64, 128, 256 or 512;
  *                           0 = each kernel's default

@@ -103,11 +103,12 @@ kvq_status stream_tiling_for(int cus, int64_t batch, int64_t N, int64_t D, int V
   // the passes option, when moved off its default of 1, overrides a kernel's own default
   int passes = o.passes_per_block != 1 ? o.passes_per_block : default_passes;
   const int block = o.block_threads > 0 ? o.block_threads : default_block;
-  Tiling t = make_tiling(batch, N, D, V, U, (int64_t)cus * o.blocks_per_cu, block, passes);
+  const int64_t target = (int64_t)cus * (o.blocks_per_cu > 0 ? o.blocks_per_cu : 8);  // used when passes == 0
+  Tiling t = make_tiling(batch, N, D, V, U, target, block, passes);
   // one-shot workgroups by default; fall back to longer walks only when the grid would not be indexable
   while (t.items > ((int64_t)1 << 30) && passes > 0 && passes < (1 << 20)) {
     passes *= 2;
-    t = make_tiling(batch, N, D, V, U, (int64_t)cus * o.blocks_per_cu, block, passes);
+    t = make_tiling(batch, N, D, V, U, target, block, passes);
   }
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   *U_out = U;
@@ -396,7 +397,7 @@ kvq_status kvq_set_option(int key, int value) {
       o.codec_unroll = value;
       return KVQ_OK;
     case KVQ_OPT_BLOCKS_PER_CU:
-      if (value < 1 || value > 64) return KVQ_ERR_ARG;
+      if (value < 0 || value > 64) return KVQ_ERR_ARG;
       o.blocks_per_cu = value;
       return KVQ_OK;
     case KVQ_OPT_NONTEMPORAL:

@@ -223,7 +223,11 @@ kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int6
   const bool vec = aligned(x, 16) && aligned(x_hat, 16);
   const int64_t work = vec ? count / 4 : count;           // vectors (or elements) to walk
   const int64_t tile = (int64_t)kBlock * U;
-  int64_t blocks = (int64_t)dev.cus * options().blocks_per_cu;
+  // one long contiguous chunk per compute unit: as for the scale reduction, a read-only stream runs best as
+  // one fat walk per unit (1 / 2 / 8 workgroups per unit: 7.24 / 7.15 / 7.06 TB/s on [131072 x 8192],
+  // 6.94 / 6.76 / 6.60 on [16384 x 8192])
+  const int per_cu = options().blocks_per_cu > 0 ? options().blocks_per_cu : 1;
+  int64_t blocks = (int64_t)dev.cus * per_cu;
   if (blocks > kMaxPartials) blocks = kMaxPartials;
   int64_t chunk = (work + blocks - 1) / blocks;
   chunk = (chunk + tile - 1) / tile * tile;
@@ -254,7 +258,10 @@ kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, con
   // 4 channels per lane, as in the codec kernels: every wavefront access is one contiguous segment
   int V = pick_width(D, x, codes, 4);
   if (V > 1 && !aligned(scales, 16)) V = 1;
-  const Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * options().blocks_per_cu);
+  // two workgroups per compute unit (1 / 2 / 8: 6.61 / 6.82 / 6.67 TB/s on [131072 x 8192], 6.07 / 6.10 / 5.69
+  // on [16384 x 8192], 6.06 / 6.64 / 6.47 on [256 x 4096 x 128])
+  const int per_cu = options().blocks_per_cu > 0 ? options().blocks_per_cu : 2;
+  const Tiling t = make_tiling(batch, N, D, V, U, (int64_t)dev.cus * per_cu);
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   int64_t blocks = t.items < kMaxPartials ? t.items : kMaxPartials;
   const dim3 grid((uint32_t)blocks), block(kBlock);

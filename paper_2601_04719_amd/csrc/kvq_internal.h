@@ -60,7 +60,7 @@ constexpr int kQuantUnroll = 4, kQuantBlock = 512, kDequantUnroll = 2, kDequantB
 struct Options {
   int codec_width = 4;
   int codec_unroll = 0;  // 0 = per kernel default (quantize 4, dequantize 2)
-  int blocks_per_cu = 8;
+  int blocks_per_cu = 0;  // 0 = per kernel default (error reductions: 1 dense, 2 from codes; codecs: 8)
   int nontemporal = 1;
   int block_threads = 0;  // 0 = per kernel default (quantize 512, dequantize 256)
   int passes_per_block = 1;

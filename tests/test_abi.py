@@ -72,7 +72,7 @@ def test_argument_errors_are_reported_before_any_launch():
 
 def test_options_round_trip_and_reject_bad_values():
     for key, good, bad in [(kvq.OPT_CODEC_WIDTH, 8, 3), (kvq.OPT_CODEC_UNROLL, 4, 3),
-                           (kvq.OPT_BLOCKS_PER_CU, 16, 0), (kvq.OPT_NONTEMPORAL, 0, 2),
+                           (kvq.OPT_BLOCKS_PER_CU, 16, 65), (kvq.OPT_NONTEMPORAL, 0, 2),
                            (kvq.OPT_BLOCK_THREADS, 128, 100), (kvq.OPT_PASSES_PER_BLOCK, 0, -1),
                            (kvq.OPT_ABSMAX_UNROLL, 4, 5), (kvq.OPT_ABSMAX_PASSES, 2, -1),
                            (kvq.OPT_ABSMAX_SPAN, 2, 3), (kvq.OPT_ABSMAX_BLOCKS_PER_CU, 4, 0),
