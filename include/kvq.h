@@ -24,9 +24,11 @@
  *  - the scale reductions (kvq_absmax_scales and its _t, _int4, _fp8 forms),
  *    kvq_roundtrip_error and kvq_attn_score_error keep a per-device, per-stream
  *    workspace (16 MiB of partial maxima and sums) that the library allocates with
- *    hipMalloc on a stream's first such call and never frees -- make that call
- *    outside any graph capture.  Two calls in flight on the SAME stream are
- *    ordered by the stream; calls on different streams use different workspaces.
+ *    hipMalloc on a stream's first such call (or in kvq_prepare_stream) and never
+ *    frees -- make that call outside any graph capture.  Two calls in flight on
+ *    the SAME stream are ordered by the stream; calls on different streams use
+ *    different workspaces.  kvq_append and kvq_quantize_fused run a scale
+ *    reduction and so use it too.
  *  - results of kvq_absmax_scales, kvq_quantize, kvq_dequantize are unique bit
  *    patterns; the error statistics are deterministic for a given shape.
  */
@@ -340,6 +342,13 @@ int kvq_last_hip_error(void);
 #define KVQ_OPT_ABSMAX_SPAN 10
 #define KVQ_OPT_ABSMAX_BLOCKS_PER_CU 11
 #define KVQ_OPT_APPEND_BLOCKS_PER_CU 12
+/*
+ * Creates the current device's workspace for `stream` now (one hipMalloc; nothing happens if it
+ * exists), so that the first reduction on that stream allocates nothing -- call it before capturing
+ * a graph on the stream, or before entering a region that must not allocate.
+ */
+kvq_status kvq_prepare_stream(kvq_stream_t stream);
+
 /*
  * The launch plan of a streaming call for a shape, computed on the host without touching a
  * device: how scale reduction, quantize or dequantize (fp32 matrices, current options) would

@@ -261,6 +261,11 @@ kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int
   return launch_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
 }
 
+kvq_status kvq_prepare_stream(kvq_stream_t stream) {
+  Workspace ws;
+  return get_workspace(stream, &ws);
+}
+
 kvq_status kvq_plan(int call, int64_t batch, int64_t N, int64_t D, int vector_access, int compute_units,
                     int64_t* plan_out) {
   if (!plan_out) return KVQ_ERR_NULL;

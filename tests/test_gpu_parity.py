@@ -953,8 +953,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         return [t.clone() for t in (g.scales, g.codes, g.xh, g.sumsq, g.maxabs, s4, packed)]
 
     side = torch.cuda.Stream()
-    with torch.cuda.stream(side):
-        step()                                  # creates this stream's workspace outside the capture
+    kvq.kvq_prepare_stream(side.cuda_stream)    # this stream's workspace exists before the capture
     side.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
