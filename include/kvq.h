@@ -58,8 +58,8 @@ typedef struct ihipStream_t *kvq_stream_t;
  * Scales": scales[b,d] = max_t |x[b,t,d]| / 127 (one IEEE fp32 divide), +0 for
  * an all-zero channel.
  *   x      [batch,N,D] fp32, device, read only
- *   scales [batch,D]   fp32, device, written (also used as reduction scratch
- *                      while the call runs; needs 4-byte alignment only)
+ *   scales [batch,D]   fp32, device, written once per channel (4-byte alignment
+ *                      suffices); partial maxima live in the stream's workspace
  */
 kvq_status kvq_absmax_scales(const float *x, float *scales,
                              int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
