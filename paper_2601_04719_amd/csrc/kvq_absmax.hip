@@ -187,10 +187,11 @@ kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, i
     const int jmax = elements >= ((int64_t)cus << 22) ? 8 : 4;
     while (J < o.absmax_span && J < jmax && (int64_t)kBlock * J < groups) J *= 2;
   }
-  // rows in flight: J * U 16-byte loads per lane, at most 16
+  // rows in flight: with several column groups per lane J * U 16-byte loads, at most 8 (16 measured 1-4 % slower on D = 8192 with
+  // 16384 to 131072 rows, 32 slower still: one workgroup per compute unit wants a short loop, not depth)
   int U = o.absmax_unroll;
-  while (J * U > 16) U /= 2;
-  if (J >= 2 && U > 4) U = 4;
+  if (J >= 2)
+    while (J * U > 8 && U > 1) U /= 2;
   int passes = o.absmax_passes;
   // tiling in units of J * V channels per lane
   Tiling t = make_tiling(batch, N, D, V * J, U, (int64_t)cus * o.absmax_blocks_per_cu, kBlock, passes);
@@ -232,12 +233,9 @@ kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, in
   const bool nt = o.nontemporal != 0;
   kvq_status s;
 #define KVQ_AM(V_, J_, U_) s = launch_absmax_t<V_, J_, U_>(x, dst, total, qmax, N, D, t, nt, stream)
-  if (V == 4 && J == 8 && U == 4) KVQ_AM(4, 8, 4);
-  else if (V == 4 && J == 8) KVQ_AM(4, 8, 2);
-  else if (V == 4 && J == 4 && U == 4) KVQ_AM(4, 4, 4);
+  if (V == 4 && J == 8) KVQ_AM(4, 8, 1);
   else if (V == 4 && J == 4) KVQ_AM(4, 4, 2);
-  else if (V == 4 && J == 2 && U == 4) KVQ_AM(4, 2, 4);
-  else if (V == 4 && J == 2) KVQ_AM(4, 2, 2);
+  else if (V == 4 && J == 2) KVQ_AM(4, 2, 4);
   else if (V == 4 && U == 4) KVQ_AM(4, 1, 4);
   else if (V == 4 && U == 8) KVQ_AM(4, 1, 8);
   else if (V == 4) KVQ_AM(4, 1, 16);
