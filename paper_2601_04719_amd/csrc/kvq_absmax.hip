@@ -20,7 +20,7 @@
 // reads whole rows -- one fat contiguous stream per compute unit.  Measured on
 // the 1B-element shape: 7.0 TB/s, against 6.5 TB/s with eight 4 KiB-wide
 // workgroups per compute unit, and 4 TB/s for one-shot workgroups of a few rows
-// (each ending in a store per channel).
+// (measured when every workgroup still ended in an atomic per channel).
 #include <type_traits>
 
 #include "kvq_internal.h"
