@@ -213,6 +213,77 @@ __global__ __launch_bounds__(kBlock) void roundtrip_codes_kernel(const float* __
   }
 }
 
+// Wide rows (D >= 2048 channels): the lanes of a workgroup own J column groups each, 256 groups apart,
+// so that the workgroup reads whole rows -- one fat contiguous stream of x and one of codes per
+// workgroup, as in the scale reduction -- with the J * 4 scales of a lane in registers.
+template <int J>
+__global__ __launch_bounds__(kBlock) void roundtrip_codes_rows_kernel(const float* __restrict__ x,
+                                                                      const int8_t* __restrict__ codes,
+                                                                      const float* __restrict__ scales, int64_t N,
+                                                                      int64_t D, uint32_t ctiles, uint32_t rchunks,
+                                                                      int64_t rows_per_chunk, int64_t groups,
+                                                                      uint32_t items, double* __restrict__ sums,
+                                                                      float* __restrict__ maxes) {
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  float mx = 0.0f;
+  for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
+    const uint32_t ct = item % ctiles, rest = item / ctiles;
+    const uint32_t rc = rest % rchunks;
+    const int64_t slab = rest / rchunks;
+    const int64_t group0 = (int64_t)ct * kBlock * J + threadIdx.x;
+    const int64_t row0 = (int64_t)rc * rows_per_chunk;
+    int64_t row1 = row0 + rows_per_chunk;
+    if (row1 > N) row1 = N;
+    f32x4 s[J];
+    bool act[J];
+#pragma unroll
+    for (int j = 0; j < J; j++) {
+      act[j] = group0 + (int64_t)j * kBlock < groups;
+      s[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (act[j]) s[j] = *reinterpret_cast<const f32x4*>(scales + slab * D + (group0 + (int64_t)j * kBlock) * 4);
+    }
+    const float* px = x + (slab * N + row0) * D + group0 * 4;
+    const int8_t* pc = codes + (slab * N + row0) * D + group0 * 4;
+    // U = 8 / J rows at a time: eight 16-byte and eight 4-byte loads in flight per lane
+    constexpr int U = 8 / J;
+    auto do_rows = [&](auto tag) {
+      constexpr int R = decltype(tag)::value;
+      f32x4 v[R][J];
+      uint32_t w[R][J];
+#pragma unroll
+      for (int u = 0; u < R; u++)
+#pragma unroll
+        for (int j = 0; j < J; j++) {
+          v[u][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+          w[u][j] = 0u;
+          if (act[j]) {
+            v[u][j] = ld<true>(reinterpret_cast<const f32x4*>(px + u * D) + (int64_t)j * kBlock);
+            w[u][j] = ld<true>(reinterpret_cast<const uint32_t*>(pc + u * D) + (int64_t)j * kBlock);
+          }
+        }
+#pragma unroll
+      for (int u = 0; u < R; u++)
+#pragma unroll
+        for (int j = 0; j < J; j++)
+#pragma unroll
+          for (int b = 0; b < 4; b++) {
+            const int q = (int)(w[u][j] << (24 - 8 * b)) >> 24;
+            const float xh = (float)q * s[j][b];   // inactive groups: 0 * 0 against x = 0
+            err_step(v[u][j][b], xh, acc[b], mx);
+          }
+    };
+    int64_t row = row0;
+    for (; row + U <= row1; row += U, px += U * D, pc += U * D) do_rows(std::integral_constant<int, U>{});
+    for (; row < row1; row++, px += D, pc += D) do_rows(std::integral_constant<int, 1>{});
+  }
+  double sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  block_reduce(sum, mx);
+  if (threadIdx.x == 0) {
+    sums[blockIdx.x] = sum;
+    maxes[blockIdx.x] = mx;
+  }
+}
+
 kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int64_t count, double* sumsq_out,
                                         float* maxabs_out, hipStream_t stream) {
   const DeviceInfo dev = current_device();
@@ -258,6 +329,35 @@ kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, con
   // 4 channels per lane, as in the codec kernels: every wavefront access is one contiguous segment
   int V = pick_width(D, x, codes, 4);
   if (V > 1 && !aligned(scales, 16)) V = 1;
+  if (V == 4 && D >= 2048) {
+    // rows at least two workgroup-widths wide: row-spanning lanes, one or two workgroups per compute unit
+    const int64_t groups = D / 4;
+    int J = 1;
+    while (J < 8 && (int64_t)kBlock * J * 2 <= groups) J *= 2;
+    const int64_t ctiles = (groups + (int64_t)kBlock * J - 1) / ((int64_t)kBlock * J);
+    const int per_cu = options().blocks_per_cu > 0 ? options().blocks_per_cu : 2;
+    int64_t want = ((int64_t)dev.cus * per_cu + batch * ctiles - 1) / (batch * ctiles);
+    if (want < 1) want = 1;
+    if (want > N) want = N;
+    const int64_t rows = (N + want - 1) / want;
+    const int64_t rchunks = (N + rows - 1) / rows;
+    const int64_t items = batch * rchunks * ctiles;
+    if (items > INT32_MAX) return KVQ_ERR_OVERFLOW;
+    const int64_t nblocks = items < kMaxPartials ? items : kMaxPartials;
+    const dim3 grid((uint32_t)nblocks), block(kBlock);
+#define KVQ_LAUNCH_RR(J_)                                                                                       \
+  hipLaunchKernelGGL((roundtrip_codes_rows_kernel<J_>), grid, block, 0, stream, x, codes, scales, N, D,         \
+                     (uint32_t)ctiles, (uint32_t)rchunks, rows, groups, (uint32_t)items, ws.sums, ws.maxes)
+    if (J == 8) KVQ_LAUNCH_RR(8);
+    else if (J == 4) KVQ_LAUNCH_RR(4);
+    else KVQ_LAUNCH_RR(2);
+#undef KVQ_LAUNCH_RR
+    KVQ_HIP(hipGetLastError());
+    hipLaunchKernelGGL(fold_partials, dim3(1), dim3(kBlock), 0, stream, ws.sums, ws.maxes, (int)nblocks, 1.0,
+                       sumsq_out, maxabs_out);
+    KVQ_HIP(hipGetLastError());
+    return KVQ_OK;
+  }
   // two workgroups per compute unit (1 / 2 / 8: 6.61 / 6.82 / 6.67 TB/s on [131072 x 8192], 6.07 / 6.10 / 5.69
   // on [16384 x 8192], 6.06 / 6.64 / 6.47 on [256 x 4096 x 128])
   const int per_cu = options().blocks_per_cu > 0 ? options().blocks_per_cu : 2;
