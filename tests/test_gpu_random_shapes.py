@@ -61,3 +61,71 @@ def test_random_shapes_offsets_and_entry_points(seed):
             T.assert_bits_equal(sc, s_ref, tag + " fused scales")
             T.assert_bits_equal(cd, oracle.quantize(x, s_ref), tag + " fused codes")
             assert g.guards_intact(), tag
+
+
+@pytest.mark.parametrize("seed", [10, 11])
+def test_random_shapes_sixteen_bit_inputs_and_wide_rows(seed):
+    """fp16 / bf16 matrices and appended tokens, and fp32 round trips on rows wide enough for the
+    row-spanning reductions, with up to 3 M elements so that slabs split into many row chunks."""
+    import torch
+    from paper_2601_04719_amd import kvq
+    rng = np.random.default_rng(seed)
+    for case in range(70):
+        kind = int(rng.integers(0, 3))
+        D = int(rng.choice(WIDTHS if kind < 2 else [2048, 2052, 4096, 6144, 8192, 8200, 16384]))
+        batch = int(rng.choice([1, 1, 2, 3]))
+        N = int(rng.integers(1, max(2, int(rng.choice([200000, 3000000])) // (D * batch))))
+        off = int(rng.choice([0, 0, 0, 1, 2, 4, 8, 16]))
+        fmt = str(rng.choice(["f16", "bf16"]))
+        dt = kvq.DTYPE_F16 if fmt == "f16" else kvq.DTYPE_BF16
+        tag = "seed %d case %d: kind %d %s shape (%d,%d,%d) offset %d" % (seed, case, kind, fmt, batch, N, D, off)
+        print(tag, flush=True)
+        x = T.make_matrix(rng, batch, N, D)
+        if kind == 0:
+            x16 = oracle.narrow16(np.clip(x, -60000, 60000), fmt)
+            xw = oracle.widen16(x16, fmt)
+            s_ref = oracle.compute_scales(xw)
+            q_ref = oracle.quantize(xw, s_ref)
+            xh_ref = oracle.dequantize_as(q_ref, s_ref, fmt)
+            n = x.size
+            xd = torch.zeros(n + 16, dtype=torch.int16, device="cuda")
+            xd[off:off + n].copy_(torch.from_numpy(x16.view(np.int16).reshape(-1)))
+            scales = torch.full((batch * D + 16,), -5.0, dtype=torch.float32, device="cuda")
+            codes = torch.full((n + 16,), 99, dtype=torch.int8, device="cuda")
+            xh = torch.full((n + 16,), 12345, dtype=torch.int16, device="cuda")
+            sv, cv, hv, xv = scales[off:], codes[off:], xh[off:], xd[off:]
+            kvq.kvq_absmax_scales_t(dt, xv, sv, batch, N, D)
+            kvq.kvq_quantize_t(dt, xv, sv, cv, batch, N, D)
+            kvq.kvq_dequantize_t(dt, cv, sv, hv, batch, N, D)
+            T.assert_bits_equal(sv[:batch * D].cpu().numpy().reshape(batch, D), s_ref, tag + " scales")
+            T.assert_bits_equal(cv[:n].cpu().numpy().reshape(x.shape), q_ref, tag + " codes")
+            assert np.array_equal(hv[:n].cpu().numpy().view(np.uint16).reshape(x.shape), xh_ref), tag + " x_hat"
+            assert bool((codes[:off] == 99).all() and (codes[off + n:] == 99).all()), tag
+            assert bool((xh[:off] == 12345).all() and (xh[off + n:] == 12345).all()), tag
+            assert bool((scales[:off] == -5.0).all() and (scales[off + batch * D:] == -5.0).all()), tag
+        elif kind == 1:
+            cap = N + int(rng.integers(0, 5))
+            g = T.GpuCache(batch, cap, D, off)
+            ref_codes = np.full((batch, cap, D), 55, dtype=np.int8)
+            ref_scales = np.zeros((batch, D), dtype=np.float32)
+            xs = T.growing_tokens(rng, batch, N, D) if N > 1 else x
+            x16 = oracle.narrow16(np.clip(xs, -60000, 60000), fmt)
+            xw = oracle.widen16(x16, fmt)
+            done = 0
+            while done < N:
+                m = int(min(N - done, rng.choice([1, 1, 2, 7, 16, 17, 40, 300, 5000])))
+                tok = np.ascontiguousarray(x16[:, done:done + m])
+                buf = torch.zeros(tok.size + 64, dtype=torch.int16, device="cuda")
+                xv = buf[off:off + tok.size]
+                xv.copy_(torch.from_numpy(tok.view(np.int16).reshape(-1)))
+                kvq.kvq_append_t(dt, xv, g.scales, g.prev, g.codes, batch, done, m, cap, D)
+                ref_codes, ref_scales, _ = oracle.append(ref_codes, ref_scales, done,
+                                                         np.ascontiguousarray(xw[:, done:done + m]))
+                done += m
+            codes, scales, _ = g.state()
+            T.assert_bits_equal(scales, ref_scales, tag + " scales")
+            T.assert_bits_equal(codes, ref_codes, tag + " cache")
+            assert g.guards_intact(), tag
+        else:
+            qs = rng.standard_normal((3, D)).astype(np.float32) if batch == 1 else None
+            T.full_round_trip_check(x, qs, offset=off, tag=tag)
