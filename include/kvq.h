@@ -24,8 +24,9 @@
  *  - the scale reductions (kvq_absmax_scales and its _t, _int4, _fp8 forms),
  *    kvq_roundtrip_error and kvq_attn_score_error keep a per-device, per-stream
  *    workspace (16 MiB of partial maxima and sums) that the library allocates with
- *    hipMalloc on a stream's first such call (or in kvq_prepare_stream) and never
- *    frees -- make that call outside any graph capture.  Two calls in flight on
+ *    hipMalloc on a stream's first such call (or in kvq_prepare_stream) and keeps
+ *    until kvq_release_stream or the end of the process -- make that call outside
+ *    any graph capture.  Two calls in flight on
  *    the SAME stream are ordered by the stream; calls on different streams use
  *    different workspaces.  kvq_append and kvq_quantize_fused run a scale
  *    reduction and so use it too.
@@ -348,6 +349,13 @@ int kvq_last_hip_error(void);
  * a graph on the stream, or before entering a region that must not allocate.
  */
 kvq_status kvq_prepare_stream(kvq_stream_t stream);
+
+/*
+ * Frees the current device's workspace of `stream` (hipFree, which waits for the device), e.g.
+ * before the stream is destroyed.  No library call may be in flight on that stream.  Without
+ * this call a workspace lives until the process ends.  KVQ_OK also when there is none.
+ */
+kvq_status kvq_release_stream(kvq_stream_t stream);
 
 /*
  * The launch plan of a streaming call for a shape, computed on the host without touching a

@@ -116,15 +116,18 @@ kvq_status stream_tiling_for(int cus, int64_t batch, int64_t N, int64_t D, int V
   return KVQ_OK;
 }
 
+namespace {
+std::mutex g_ws_mutex;
+std::map<std::pair<int, hipStream_t>, Workspace> g_ws_table;
+}  // namespace
+
 kvq_status get_workspace(hipStream_t stream, Workspace* out) {
-  static std::mutex mu;
-  static std::map<std::pair<int, hipStream_t>, Workspace> table;
   int dev = -1;
   KVQ_HIP(hipGetDevice(&dev));
-  std::lock_guard<std::mutex> lock(mu);
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
   auto key = std::make_pair(dev, stream);
-  auto it = table.find(key);
-  if (it != table.end()) {
+  auto it = g_ws_table.find(key);
+  if (it != g_ws_table.end()) {
     *out = it->second;
     return KVQ_OK;
   }
@@ -134,8 +137,23 @@ kvq_status get_workspace(hipStream_t stream, Workspace* out) {
   w.sums = static_cast<double*>(p);
   w.maxes = reinterpret_cast<float*>(w.sums + kMaxPartials);
   w.colmax = w.maxes + kMaxPartials;
-  table[key] = w;
+  g_ws_table[key] = w;
   *out = w;
+  return KVQ_OK;
+}
+
+kvq_status release_workspace(hipStream_t stream) {
+  int dev = -1;
+  KVQ_HIP(hipGetDevice(&dev));
+  void* p = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    auto it = g_ws_table.find(std::make_pair(dev, stream));
+    if (it == g_ws_table.end()) return KVQ_OK;
+    p = it->second.sums;  // start of the one allocation
+    g_ws_table.erase(it);
+  }
+  KVQ_HIP(hipFree(p));
   return KVQ_OK;
 }
 
@@ -265,6 +283,8 @@ kvq_status kvq_prepare_stream(kvq_stream_t stream) {
   Workspace ws;
   return get_workspace(stream, &ws);
 }
+
+kvq_status kvq_release_stream(kvq_stream_t stream) { return release_workspace(stream); }
 
 kvq_status kvq_plan(int call, int64_t batch, int64_t N, int64_t D, int vector_access, int compute_units,
                     int64_t* plan_out) {

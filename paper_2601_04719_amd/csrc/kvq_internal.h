@@ -103,6 +103,8 @@ struct Workspace {
   float* colmax;  // [kColmaxFloats]: [row chunk][batch * D]
 };
 kvq_status get_workspace(hipStream_t stream, Workspace* out);
+// frees the current device's workspace of `stream`, if there is one
+kvq_status release_workspace(hipStream_t stream);
 
 // ---- launchers (each validates nothing: the C-ABI layer has done that) ----
 // scales = column absmax / qmax (127 for 8-bit codes, 7 for 4-bit codes)

@@ -23,7 +23,7 @@ OPT_APPEND_BLOCKS_PER_CU = 12
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
-    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_plan", "kvq_prepare_stream",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_plan", "kvq_prepare_stream", "kvq_release_stream",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
@@ -77,6 +77,8 @@ def lib():
         L.kvq_plan.restype = i32
         L.kvq_prepare_stream.argtypes = [p]
         L.kvq_prepare_stream.restype = i32
+        L.kvq_release_stream.argtypes = [p]
+        L.kvq_release_stream.restype = i32
         L.kvq_quantize_variant.argtypes = [i32, p, p, p, i64, i64, i64, p]
         L.kvq_quantize_variant.restype = i32
         L.kvq_scores_from_codes.argtypes = [p, i64, p, p, i64, i64, i64, p, p]
@@ -205,6 +207,10 @@ def kvq_append_t(dtype, x_new, scales, scales_prev, codes, batch, n_old, m, capa
 
 def kvq_prepare_stream(stream=None):
     _check(lib().kvq_prepare_stream(_stream(stream)), "kvq_prepare_stream")
+
+
+def kvq_release_stream(stream=None):
+    _check(lib().kvq_release_stream(_stream(stream)), "kvq_release_stream")
 
 
 PLAN_ABSMAX, PLAN_QUANTIZE, PLAN_DEQUANTIZE = 0, 1, 2

@@ -643,6 +643,23 @@ def test_streams_do_not_share_scratch():
         assert float(g.sumsq.item()) == pytest.approx(ss_ref, rel=REL) and np.float32(g.maxabs.item()) == mx_ref
 
 
+def test_a_streams_workspace_can_be_released_and_comes_back():
+    x = make_matrix(np.random.default_rng(8), 1, 9000, 256)
+    s_ref = oracle.compute_scales(x)
+    g = Gpu(x)
+    torch.cuda.synchronize()                        # the input copy ran on the default stream
+    st = torch.cuda.Stream()
+    h = st.cuda_stream
+    kvq.kvq_release_stream(h)                       # nothing there yet: still OK
+    kvq.kvq_prepare_stream(h)
+    for _ in range(3):
+        kvq.kvq_absmax_scales(g.x, g.scales, 1, g.N, g.D, stream=h)
+        st.synchronize()
+        assert_bits_equal(g.scales.cpu().numpy().reshape(s_ref.shape), s_ref, "scales")
+        kvq.kvq_release_stream(h)                   # the next call allocates a fresh workspace
+    kvq.kvq_release_stream(h)
+
+
 # ------------------------------------------------------------------ 4-bit codes
 def int4_round_trip(x, offset=0, given_scales=None):
     """kvq_*_int4 against the oracle's qmax = 7 functions: scales, packed bytes and x_hat bit-exact,
