@@ -245,9 +245,10 @@ def unpack_int4(packed):
 # from their reconstruction:  code' = Q(code * s_old ; s_new), with Q and the product being
 # Eq. (quant_op) and Eq. (dequant_op).  Built from the functions above, nothing else.
 # ---------------------------------------------------------------------------------------------
-def append(codes, scales, n_old, x_new):
-    """codes [batch, capacity, D] int8 (rows [0, n_old) valid), scales [batch, D], x_new [batch, m, D].
+def append_q(codes, scales, n_old, x_new, qmax):
+    """Streaming append with the integer range [-qmax, qmax] (127: 8-bit codes, 7: 4-bit codes).
 
+    codes [batch, capacity, D] int8 (rows [0, n_old) valid), scales [batch, D], x_new [batch, m, D].
     Returns (codes', scales', scales_prev): rows [0, n_old + m) of codes' valid, the rest untouched."""
     codes = np.ascontiguousarray(codes)
     x_new = _f32(x_new)
@@ -258,16 +259,21 @@ def append(codes, scales, n_old, x_new):
     s_old = _f32(scales).reshape(batch, D)
     if x_new.shape[0] != batch or x_new.shape[2] != D or not (0 <= n_old and n_old + m <= cap):
         raise ValueError("shape mismatch or capacity exceeded")
-    cand = compute_scales(x_new).reshape(batch, D)                 # absmax of the new tokens / 127
+    cand = compute_scales_q(x_new, qmax).reshape(batch, D)         # absmax of the new tokens / qmax
     s_new = np.where(cand > s_old, cand, s_old).astype(np.float32)
     grew = s_new > s_old                                           # [batch, D]
     out = codes.copy()
     if n_old:
         cached = np.ascontiguousarray(codes[:, :n_old])
-        again = quantize(dequantize(cached, s_old), s_new)         # reconstruction, then the new scale
+        again = quantize_q(dequantize(cached, s_old), s_new, qmax)  # reconstruction, then the new scale
         out[:, :n_old] = np.where(grew[:, None, :], again, cached)
-    out[:, n_old:n_old + m] = quantize(x_new, s_new)
+    out[:, n_old:n_old + m] = quantize_q(x_new, s_new, qmax)
     return out, s_new, s_old.copy()
+
+
+def append(codes, scales, n_old, x_new):
+    """append_q for 8-bit codes."""
+    return append_q(codes, scales, n_old, x_new, 127)
 
 
 # ---------------------------------------------------------------------------------------------

@@ -536,6 +536,50 @@ def test_append_from_empty_equals_batch_and_scales_track_the_running_absmax():
     assert (np.abs(cache[:, :N].astype(np.int32)) <= 127).all()
 
 
+def test_append_with_four_bit_codes_hand_worked_and_properties():
+    # range [-7, 7]: channel 0 grows 1 -> 2 (new token 14 = 7 * 2): cached 7, 4, 3, -1, 0 become
+    # 3.5 -> 4 (tie to even), 2, 1.5 -> 2, -0.5 -> 0, 0.  Channel 1 (scale 0.5) keeps its codes; 1.0 -> 2.
+    cache = np.zeros((1, 8, 2), dtype=np.int8)
+    cache[0, :5, 0] = [7, 4, 3, -1, 0]
+    cache[0, :5, 1] = [7, -5, 1, 0, 6]
+    cache[0, 5:] = 99
+    s = np.array([[1.0, 0.5]], dtype=np.float32)
+    out, s_new, prev = oracle.append_q(cache, s, 5, np.array([[[14.0, 1.0]]], dtype=np.float32), 7)
+    assert s_new.tolist() == [[2.0, 0.5]] and prev.tolist() == [[1.0, 0.5]]
+    assert out[0, :6, 0].tolist() == [4, 2, 2, 0, 0, 7]
+    assert out[0, :6, 1].tolist() == [7, -5, 1, 0, 6, 2]
+    assert (out[0, 6:] == 99).all()
+    # qmax = 127 is the 8-bit append
+    rng = np.random.default_rng(43)
+    B, N, D = 2, 60, 6
+    x = (rng.standard_normal((B, N, D)) * np.exp(rng.uniform(-2, 2, (B, 1, D)))).astype(np.float32)
+    x[:, :, 2] *= np.linspace(0.1, 3.0, N)[None, :]
+    c8 = np.full((B, 64, D), 55, dtype=np.int8)
+    a = oracle.append(c8, np.zeros((B, D), np.float32), 0, x[:, :20])
+    b = oracle.append_q(c8, np.zeros((B, D), np.float32), 0, x[:, :20], 127)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    # 4-bit: everything at once onto an empty cache is the batch method; chunked, the scales track the
+    # running absmax / 7 and channels that never grew hold the batch codes
+    cache = np.full((B, 64, D), 55, dtype=np.int8)
+    out, s1, _ = oracle.append_q(cache, np.zeros((B, D), np.float32), 0, x, 7)
+    assert np.array_equal(s1, oracle.compute_scales_q(x, 7))
+    assert np.array_equal(out[:, :N], oracle.quantize_q(x, s1, 7)) and (out[:, N:] == 55).all()
+    s, n, grow_events = np.zeros((B, D), dtype=np.float32), 0, np.zeros((B, D), dtype=np.int64)
+    for m in (1, 5, 1, 23, 30):
+        cache, s_next, prev = oracle.append_q(cache, s, n, x[:, n:n + m], 7)
+        assert np.array_equal(prev, s)
+        grow_events += (s_next > s) & (n > 0)
+        s, n = s_next, n + m
+        assert np.array_equal(s, oracle.compute_scales_q(x[:, :n], 7))
+    assert (np.abs(cache[:, :N].astype(np.int32)) <= 7).all() and (cache[:, N:] == 55).all()
+    never = grow_events == 0
+    same = cache[:, :N] == oracle.quantize_q(x, s, 7)
+    assert not never[:, 2].any() and same[np.broadcast_to(never[:, None, :], same.shape)].all()
+    err = np.abs(x.astype(np.float64) - oracle.dequantize(np.ascontiguousarray(cache[:, :N]), s))
+    bound = (grow_events + 1)[:, None, :] * s.astype(np.float64)[:, None, :] / 2 * (1 + 2.0 ** -15)
+    assert (err <= bound).all()
+
+
 # --------------------------------------------------------------------------
 # FP8 (E4M3) codes
 # --------------------------------------------------------------------------
