@@ -182,6 +182,21 @@ kvq_status kvq_append_t(int dtype, const void *x_new, float *scales, float *scal
                         kvq_stream_t stream);
 
 /*
+ * The same append onto a 4-bit cache (kvq_quantize_int4's packed layout; Limitations, "Lower
+ * bit-widths" together with "Dynamic quantization"): the formulas of kvq_append with 127 replaced
+ * by 7 -- cand = absmax / 7, codes clamped to [-7, 7], cached codes of grown channels re-expressed
+ * from (float)code * s_old -- and two codes per byte.
+ *   x_new  [batch,m,D] fp32, device, read only
+ *   scales, scales_prev as for kvq_append
+ *   packed [batch,capacity,D/2] uint8, device: rows [0,n_old) read and possibly rewritten,
+ *          rows [n_old,n_old+m) written, later rows untouched
+ * D must be even (KVQ_ERR_ARG); other errors as for kvq_append.
+ */
+kvq_status kvq_append_int4(const float *x_new, float *scales, float *scales_prev, uint8_t *packed,
+                           int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D,
+                           kvq_stream_t stream);
+
+/*
  * Scale computation and quantization in one call (same results as
  * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
  * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in

@@ -329,6 +329,17 @@ kvq_status kvq_append_t(int dtype, const void* x_new, float* scales, float* scal
   return launch_append_16(dtype, x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream);
 }
 
+kvq_status kvq_append_int4(const float* x_new, float* scales, float* scales_prev, uint8_t* packed, int64_t batch,
+                           int64_t n_old, int64_t m, int64_t capacity, int64_t D, kvq_stream_t stream) {
+  if (!x_new || !scales || !scales_prev || !packed) return KVQ_ERR_NULL;
+  if (n_old < 0 || m < 1) return KVQ_ERR_SHAPE;
+  if (kvq_status s = check_shape(batch, capacity, D)) return s;
+  if (D % 2) return KVQ_ERR_ARG;
+  if (m > capacity || n_old > capacity - m) return KVQ_ERR_ARG;
+  if (scales == scales_prev) return KVQ_ERR_ARG;
+  return launch_append_int4(x_new, scales, scales_prev, packed, batch, n_old, m, capacity, D, stream);
+}
+
 kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N,
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;

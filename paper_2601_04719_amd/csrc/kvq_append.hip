@@ -225,11 +225,7 @@ static kvq_status append_t(int dtype, const typename Elem<T>::type* x_new, float
     if constexpr (std::is_same<T, float>::value) s = launch_absmax_scales(x_new, scales_prev, batch, m, D, stream);
     else s = launch_absmax_scales_16(dtype, x_new, scales_prev, batch, m, D, stream);
     if (s != KVQ_OK) return s;
-    const int64_t n = batch * D;
-    const int64_t blocks = (n + kBlock - 1) / kBlock;
-    if (blocks > INT32_MAX) return KVQ_ERR_OVERFLOW;
-    hipLaunchKernelGGL(append_merge_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, scales, scales_prev, n);
-    KVQ_HIP(hipGetLastError());
+    if (kvq_status ms = launch_append_merge(scales, scales_prev, batch * D, stream)) return ms;
   }
 
   // 2. cached rows of grown channels (rows [0, n_old) only: never the rows written by this call)
@@ -257,6 +253,14 @@ static kvq_status append_t(int dtype, const typename Elem<T>::type* x_new, float
       return launch_quantize_16_strided(dtype, x_new, scales, codes + n_old * D, batch, m, D, m * D, capacity * D,
                                         stream);
   }
+  return KVQ_OK;
+}
+
+kvq_status launch_append_merge(float* scales, float* scales_prev, int64_t n, hipStream_t stream) {
+  const int64_t blocks = (n + kBlock - 1) / kBlock;
+  if (blocks > INT32_MAX) return KVQ_ERR_OVERFLOW;
+  hipLaunchKernelGGL(append_merge_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, scales, scales_prev, n);
+  KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }
 

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kMaxBlock) void quantize_int4_kernel(const float* _
                                                                   uint8_t* __restrict__ packed, int64_t N,
                                                                   int64_t D, int tx_log2, uint32_t ctiles,
                                                                   uint32_t rchunks, int64_t rows_per_chunk,
-                                                                  int64_t groups) {
+                                                                  int64_t groups, int64_t f_slab, int64_t p_slab) {
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * 4;
@@ -45,8 +45,8 @@ __global__ __launch_bounds__(kMaxBlock) void quantize_int4_kernel(const float* _
   const int64_t step = (int64_t)it.TY * D;       // elements between the rows a lane visits
   const int64_t pstep = step >> 1;               // the same in packed bytes
   int64_t row = it.row0 + it.ty;
-  const float* px = x + (it.slab * N + row) * D + col;
-  uint8_t* pc = packed + (((it.slab * N + row) * D + col) >> 1);
+  const float* px = x + it.slab * f_slab + row * D + col;          // slab pitches: fp32 elements, packed bytes
+  uint8_t* pc = packed + it.slab * p_slab + ((row * D + col) >> 1);
 
   auto do_rows = [&](auto nrows_tag) {
     constexpr int R = decltype(nrows_tag)::value;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_int4_kernel(const uint8_
                                                                     float* __restrict__ x_hat, int64_t N,
                                                                     int64_t D, int tx_log2, uint32_t ctiles,
                                                                     uint32_t rchunks, int64_t rows_per_chunk,
-                                                                    int64_t groups) {
+                                                                    int64_t groups, int64_t f_slab, int64_t p_slab) {
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * 4;
@@ -82,8 +82,8 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_int4_kernel(const uint8_
   const int64_t step = (int64_t)it.TY * D;
   const int64_t pstep = step >> 1;
   int64_t row = it.row0 + it.ty;
-  const uint8_t* pc = packed + (((it.slab * N + row) * D + col) >> 1);
-  float* px = x_hat + (it.slab * N + row) * D + col;
+  const uint8_t* pc = packed + it.slab * p_slab + ((row * D + col) >> 1);
+  float* px = x_hat + it.slab * f_slab + row * D + col;
 
   auto do_rows = [&](auto nrows_tag) {
     constexpr int R = decltype(nrows_tag)::value;
@@ -111,15 +111,15 @@ __global__ __launch_bounds__(kMaxBlock) void quantize_int4_pair_kernel(const flo
                                                                        uint8_t* __restrict__ packed, int64_t N,
                                                                        int64_t D, int tx_log2, uint32_t ctiles,
                                                                        uint32_t rchunks, int64_t rows_per_chunk,
-                                                                       int64_t groups) {
+                                                                       int64_t groups, int64_t f_slab, int64_t p_slab) {
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * 2;
   const float s0 = divisor_of(scales[it.slab * D + col]), s1 = divisor_of(scales[it.slab * D + col + 1]);
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
-  const float* px = x + (it.slab * N + row) * D + col;
-  uint8_t* pc = packed + (((it.slab * N + row) * D + col) >> 1);
+  const float* px = x + it.slab * f_slab + row * D + col;          // slab pitches: fp32 elements, packed bytes
+  uint8_t* pc = packed + it.slab * p_slab + ((row * D + col) >> 1);
   for (; row < it.row1; row += it.TY, px += step, pc += step >> 1) {
     const uint32_t a = nibble_bits(px[0], s0) & 15u;
     const uint32_t b = nibble_bits(px[1], s1) & 15u;
@@ -132,15 +132,15 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_int4_pair_kernel(const u
                                                                          float* __restrict__ x_hat, int64_t N,
                                                                          int64_t D, int tx_log2, uint32_t ctiles,
                                                                          uint32_t rchunks, int64_t rows_per_chunk,
-                                                                         int64_t groups) {
+                                                                         int64_t groups, int64_t f_slab, int64_t p_slab) {
   const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, tx_log2);
   if (it.group >= groups) return;
   const int64_t col = it.group * 2;
   const float s0 = scales[it.slab * D + col], s1 = scales[it.slab * D + col + 1];
   const int64_t step = (int64_t)it.TY * D;
   int64_t row = it.row0 + it.ty;
-  const uint8_t* pc = packed + (((it.slab * N + row) * D + col) >> 1);
-  float* px = x_hat + (it.slab * N + row) * D + col;
+  const uint8_t* pc = packed + it.slab * p_slab + ((row * D + col) >> 1);
+  float* px = x_hat + it.slab * f_slab + row * D + col;
   for (; row < it.row1; row += it.TY, px += step, pc += step >> 1) {
     const uint32_t w = *pc;
     px[0] = dq4(w, 0, s0);
@@ -160,37 +160,42 @@ kvq_status int4_tiling(int64_t batch, int64_t N, int64_t D, const void* fp32_ptr
     const dim3 grid((uint32_t)t.items), block(t.block);                                                     \
     if (t.V == 2)                                                                                           \
       hipLaunchKernelGGL(KERNEL##_pair_kernel, grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2,        \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 1 && nt)                                                                                  \
       hipLaunchKernelGGL((KERNEL##_kernel<1, true>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2,  \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 2 && nt)                                                                                  \
       hipLaunchKernelGGL((KERNEL##_kernel<2, true>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2,  \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 4 && nt)                                                                                  \
       hipLaunchKernelGGL((KERNEL##_kernel<4, true>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2,  \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 8 && nt)                                                                                  \
       hipLaunchKernelGGL((KERNEL##_kernel<8, true>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2,  \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 1)                                                                                        \
       hipLaunchKernelGGL((KERNEL##_kernel<1, false>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2, \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 2)                                                                                        \
       hipLaunchKernelGGL((KERNEL##_kernel<2, false>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2, \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else if (U == 4)                                                                                        \
       hipLaunchKernelGGL((KERNEL##_kernel<4, false>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2, \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
     else                                                                                                    \
       hipLaunchKernelGGL((KERNEL##_kernel<8, false>), grid, block, 0, stream, __VA_ARGS__, N, D, t.tx_log2, \
-                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);                                  \
+                         t.ctiles, t.rchunks, t.rows_per_chunk, t.groups, f_slab, p_slab);                                  \
   } while (0)
 
 }  // namespace
 
 kvq_status launch_quantize_int4(const float* x, const float* scales, uint8_t* packed, int64_t batch, int64_t N,
                                 int64_t D, hipStream_t stream) {
+  return launch_quantize_int4_strided(x, scales, packed, batch, N, D, N * D, N * D / 2, stream);
+}
+
+kvq_status launch_quantize_int4_strided(const float* x, const float* scales, uint8_t* packed, int64_t batch,
+                                        int64_t N, int64_t D, int64_t f_slab, int64_t p_slab, hipStream_t stream) {
   int U;
   Tiling t;
   if (kvq_status s = int4_tiling(batch, N, D, x, packed, scales, 4, 512, &U, &t)) return s;
@@ -205,6 +210,7 @@ kvq_status launch_dequantize_int4(const uint8_t* packed, const float* scales, fl
   int U;
   Tiling t;
   if (kvq_status s = int4_tiling(batch, N, D, x_hat, packed, scales, 2, 256, &U, &t)) return s;
+  const int64_t f_slab = N * D, p_slab = N * D / 2;
   const bool nt = options().nontemporal != 0;
   KVQ_LAUNCH4(dequantize_int4, packed, scales, x_hat);
   KVQ_HIP(hipGetLastError());

@@ -121,6 +121,9 @@ void limit_row_chunks(Tiling* t, int64_t batch, int64_t N, int64_t cap);
 // 4-bit codes, two per byte (packed rows of D / 2 bytes); D is even.
 kvq_status launch_quantize_int4(const float* x, const float* scales, uint8_t* packed, int64_t batch, int64_t N,
                                 int64_t D, hipStream_t stream);
+// slab b of x starts f_slab elements after slab b-1, of packed p_slab bytes (multiples of D and D / 2)
+kvq_status launch_quantize_int4_strided(const float* x, const float* scales, uint8_t* packed, int64_t batch,
+                                        int64_t N, int64_t D, int64_t f_slab, int64_t p_slab, hipStream_t stream);
 kvq_status launch_dequantize_int4(const uint8_t* packed, const float* scales, float* x_hat, int64_t batch,
                                   int64_t N, int64_t D, hipStream_t stream);
 // FP8 (OCP E4M3) codes, one byte per element; scales = absmax / 448.
@@ -135,6 +138,11 @@ kvq_status launch_quantize_strided(const float* x, const float* scales, int8_t* 
                                    int64_t D, int64_t x_slab, int64_t c_slab, hipStream_t stream);
 // Streaming append: merge the new tokens' absmax into the scales, re-express cached codes of grown
 // channels, quantize the new tokens behind them.
+// scales_prev holds the new tokens' candidate scales on entry, the old scales on exit; scales = the larger
+kvq_status launch_append_merge(float* scales, float* scales_prev, int64_t n, hipStream_t stream);
+// 4-bit cache (packed rows of D / 2 bytes, D even), fp32 new tokens
+kvq_status launch_append_int4(const float* x_new, float* scales, float* scales_prev, uint8_t* packed, int64_t batch,
+                              int64_t n_old, int64_t m, int64_t capacity, int64_t D, hipStream_t stream);
 kvq_status launch_append(const float* x_new, float* scales, float* scales_prev, int8_t* codes, int64_t batch,
                          int64_t n_old, int64_t m, int64_t capacity, int64_t D, hipStream_t stream);
 // the same with fp16 / bf16 new tokens (dtype: KVQ_DTYPE_F16 or KVQ_DTYPE_BF16)

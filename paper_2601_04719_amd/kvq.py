@@ -23,7 +23,7 @@ OPT_APPEND_BLOCKS_PER_CU = 12
 EXPORTS = (
     "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
-    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_plan", "kvq_prepare_stream", "kvq_release_stream",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_append_int4", "kvq_plan", "kvq_prepare_stream", "kvq_release_stream",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
     "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4", "kvq_probe_stream", "kvq_status_string",
     "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
@@ -73,6 +73,8 @@ def lib():
         L.kvq_append.restype = i32
         L.kvq_append_t.argtypes = [i32, p, p, p, p, i64, i64, i64, i64, i64, p]
         L.kvq_append_t.restype = i32
+        L.kvq_append_int4.argtypes = [p, p, p, p, i64, i64, i64, i64, i64, p]
+        L.kvq_append_int4.restype = i32
         L.kvq_plan.argtypes = [i32, i64, i64, i64, i32, i32, p]
         L.kvq_plan.restype = i32
         L.kvq_prepare_stream.argtypes = [p]
@@ -198,6 +200,11 @@ def kvq_dequantize_fp8(codes, scales, x_hat, batch, N, D, stream=None):
 def kvq_append(x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):
     _check(lib().kvq_append(_addr(x_new), _addr(scales), _addr(scales_prev), _addr(codes), batch, n_old, m,
                             capacity, D, _stream(stream)), "kvq_append")
+
+
+def kvq_append_int4(x_new, scales, scales_prev, packed, batch, n_old, m, capacity, D, stream=None):
+    _check(lib().kvq_append_int4(_addr(x_new), _addr(scales), _addr(scales_prev), _addr(packed), batch, n_old, m,
+                                 capacity, D, _stream(stream)), "kvq_append_int4")
 
 
 def kvq_append_t(dtype, x_new, scales, scales_prev, codes, batch, n_old, m, capacity, D, stream=None):

@@ -116,16 +116,22 @@ def main():
                                     (32, 131072, 128, 1, "fp32"), (1, 131072, 8192, 1, "fp32"),
                                     (2048, 4096, 128, 16, "fp32"), (2048, 4096, 128, 512, "fp32"),
                                     (1, 131072, 8192, 1024, "fp32"), (2048, 4096, 128, 1, "bf16"),
-                                    (2048, 4096, 128, 512, "bf16"), (1, 131072, 8192, 1024, "bf16")]:
+                                    (2048, 4096, 128, 512, "bf16"), (1, 131072, 8192, 1024, "bf16"),
+                                    (2048, 4096, 128, 1, "fp32 onto 4-bit"), (2048, 4096, 128, 512, "fp32 onto 4-bit")]:
             n_old = cap - m
-            codes = torch.randint(-127, 128, (B * cap * D,), dtype=torch.int8, device="cuda")
+            four = fmt.endswith("4-bit")
+            qmax = 7 if four else 127
+            if four:
+                codes = torch.randint(0, 256, (B * cap * D // 2,), dtype=torch.uint8, device="cuda")
+            else:
+                codes = torch.randint(-127, 128, (B * cap * D,), dtype=torch.int8, device="cuda")
             scales0 = torch.rand(B * D, device="cuda") + 1.0
             scales = scales0.clone()
             prev = torch.empty_like(scales)
             for frac in (0.0, 0.01, 1.0):
                 # new tokens stay inside half the current range; in a fraction of the slabs (of the channels
                 # when there is one slab) they reach twice the range, so those scales grow
-                x = (torch.rand(B, m, D, device="cuda") - 0.5) * 127 * scales0.view(B, 1, D)
+                x = (torch.rand(B, m, D, device="cuda") - 0.5) * qmax * scales0.view(B, 1, D)
                 if frac > 0:
                     if B > 1:
                         x[:max(1, int(round(frac * B)))] *= 4
@@ -139,6 +145,8 @@ def main():
                     scales.copy_(scales0)          # every timed call starts from the same cache state
                     if fmt == "bf16":
                         kvq.kvq_append_t(kvq.DTYPE_BF16, x, scales, prev, codes, B, n_old, m, cap, D)
+                    elif four:
+                        kvq.kvq_append_int4(x, scales, prev, codes, B, n_old, m, cap, D)
                     else:
                         kvq.kvq_append(x, scales, prev, codes, B, n_old, m, cap, D)
 

@@ -931,6 +931,55 @@ def test_streaming_append_of_sixteen_bit_tokens(shape, chunks, offset, fmt):
     assert e.value.status == kvq.ERR_ARG
 
 
+@pytest.mark.parametrize("shape,chunks", [((3, 300, 128), (17, 1, 100, 1, 1, 64, 116)), ((2, 40, 20), (1, 16, 1, 22)),
+                                          ((1, 33, 2), (1, 1, 31)), ((4, 2100, 256), (2048, 1, 1, 50)),
+                                          ((1, 9, 4100), (1, 3, 5)), ((2, 50, 66), (20, 1, 29)), ((6, 48, 8), (48,))],
+                         ids=lambda v: "x".join(map(str, v)))
+@pytest.mark.parametrize("offset", [0, 1])
+def test_streaming_append_onto_a_four_bit_cache(shape, chunks, offset):
+    """kvq_append_int4 against the oracle's append with the range [-7, 7]: scales, previous scales and the
+    packed cache bit for bit through decode steps and prefill chunks, aligned and misaligned; bytes of
+    rows beyond the valid ones untouched."""
+    batch, cap, D = shape
+    rng = np.random.default_rng(hash((shape, offset, 4)) % (1 << 31))
+    N = sum(chunks)
+    x = growing_tokens(rng, batch, N, D)
+    nb = batch * cap * D // 2
+    pbuf = torch.full((nb + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    packed = pbuf[offset:offset + nb]
+    sbuf = torch.full((batch * D + 64,), -5.0, dtype=torch.float32, device="cuda")
+    scales = sbuf[offset:offset + batch * D]
+    scales.zero_()
+    vbuf = torch.full((batch * D + 64,), -6.0, dtype=torch.float32, device="cuda")
+    prev = vbuf[offset:offset + batch * D]
+    ref_codes = np.zeros((batch, cap, D), dtype=np.int8)
+    ref_scales = np.zeros((batch, D), dtype=np.float32)
+    n, grown_total = 0, 0
+    for m in chunks:
+        tok = np.ascontiguousarray(x[:, n:n + m])
+        buf = torch.empty(tok.size + 64, dtype=torch.float32, device="cuda")
+        xs = buf[offset:offset + tok.size]
+        xs.copy_(torch.from_numpy(tok.reshape(-1)))
+        kvq.kvq_append_int4(xs, scales, prev, packed, batch, n, m, cap, D)
+        ref_codes, new_scales, ref_prev = oracle.append_q(ref_codes, ref_scales, n, tok, 7)
+        grown_total += int(((new_scales > ref_scales) & (n > 0)).sum())
+        ref_scales, n = new_scales, n + m
+        assert_bits_equal(scales.cpu().numpy().reshape(batch, D), ref_scales, "scales after %d tokens" % n)
+        assert_bits_equal(prev.cpu().numpy().reshape(batch, D), ref_prev, "previous scales after %d tokens" % n)
+        got = packed.cpu().numpy().reshape(batch, cap, D // 2)
+        want = oracle.pack_int4(np.ascontiguousarray(ref_codes[:, :n]))
+        assert np.array_equal(got[:, :n], want), "cache after %d tokens" % n
+        assert (got[:, n:] == 0x5A).all(), "rows beyond the valid ones"
+    assert bool((pbuf[:offset] == 0x5A).all() and (pbuf[offset + nb:] == 0x5A).all())
+    assert bool((sbuf[:offset] == -5.0).all() and (sbuf[offset + batch * D:] == -5.0).all())
+    assert bool((vbuf[:offset] == -6.0).all() and (vbuf[offset + batch * D:] == -6.0).all())
+    if len(chunks) > 1:
+        assert grown_total > 0
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.kvq_append_int4(xs, scales, prev, packed, batch, 0, 1, cap, D + 1)
+    assert e.value.status == kvq.ERR_ARG
+
+
 def test_streaming_append_argument_errors():
     g = GpuCache(1, 8, 4)
     x = torch.zeros(4 * 4, dtype=torch.float32, device="cuda")
