@@ -57,9 +57,9 @@ def committed_traffic(kernel, workload):
 
 
 def time_extras(kvq, torch, stream, h, x, x_hat, codes, scales, E, N, D):
-    """Mean ms of 10 launches (after 3) of the entry points outside the timed step, on the workload's buffers."""
+    """Mean ms of 10 launches (after 5) of the entry points outside the timed step, on the workload's buffers."""
     def t(f):
-        for _ in range(3):
+        for _ in range(5):
             f()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
@@ -107,6 +107,22 @@ def time_extras(kvq, torch, stream, h, x, x_hat, codes, scales, E, N, D):
     s3 = s2.clone()
     ms = t(lambda: kvq.kvq_append(tok, s3, prev, codes, B, 4095, 1, 4096, 128, stream=h))
     out["append_one_token_no_growth"] = {"ms": round(ms, 4), "cache": "[%d x 4096 x 128]" % B}
+    tok16 = tok.to(torch.bfloat16)
+    ms = t(lambda: kvq.kvq_append_t(kvq.DTYPE_BF16, tok16, s3, prev, codes, B, 4095, 1, 4096, 128, stream=h))
+    out["append_one_bf16_token_no_growth"] = {"ms": round(ms, 4), "cache": "[%d x 4096 x 128]" % B}
+    tok4 = tok * (7.0 / 127.0)                          # inside the 4-bit range of the same scales
+    ms = t(lambda: kvq.kvq_append_int4(tok4, s3, prev, p4, B // 2, 4095, 1, 4096, 128, stream=h))
+    out["append_int4_one_token_no_growth"] = {"ms": round(ms, 4), "cache": "[%d x 4096 x 128] 4-bit" % (B // 2)}
+    # the workload as a bf16 matrix (2 B in, 1 B out per element)
+    x16 = x.to(torch.bfloat16)
+    kvq.kvq_absmax_scales_t(kvq.DTYPE_BF16, x16, scales, 1, N, D, stream=h)
+    out["quantize_bf16"] = row(t(lambda: kvq.kvq_quantize_t(kvq.DTYPE_BF16, x16, scales, codes, 1, N, D,
+                                                            stream=h)), 3.0 * E)
+    out["quantize_bf16"]["note"] = ("bound by the vector ALUs (IEEE divide), so it follows the shader clock: 0.55-0.57 ms "
+                                    "after a short warm-up, about 0.70 ms late in a long hot run such as this one")
+    out["dequantize_bf16"] = row(t(lambda: kvq.kvq_dequantize_t(kvq.DTYPE_BF16, codes, scales, x16, 1, N, D,
+                                                                stream=h)), 3.0 * E)
+    del x16
     scales.copy_(saved)
     return out
 
