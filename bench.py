@@ -118,8 +118,8 @@ def time_extras(kvq, torch, stream, h, x, x_hat, codes, scales, E, N, D):
     kvq.kvq_absmax_scales_t(kvq.DTYPE_BF16, x16, scales, 1, N, D, stream=h)
     out["quantize_bf16"] = row(t(lambda: kvq.kvq_quantize_t(kvq.DTYPE_BF16, x16, scales, codes, 1, N, D,
                                                             stream=h)), 3.0 * E)
-    out["quantize_bf16"]["note"] = ("bound by the vector ALUs (IEEE divide), so it follows the shader clock: 0.55-0.57 ms "
-                                    "after a short warm-up, about 0.70 ms late in a long hot run such as this one")
+    out["quantize_bf16"]["note"] = ("the kernel with the highest vector-ALU load (76 % busy), so it follows the shader "
+                                    "clock: 0.49 ms after a short warm-up, about 0.6 ms late in a long hot run such as this one")
     out["dequantize_bf16"] = row(t(lambda: kvq.kvq_dequantize_t(kvq.DTYPE_BF16, codes, scales, x16, 1, N, D,
                                                                 stream=h)), 3.0 * E)
     del x16

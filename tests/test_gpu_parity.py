@@ -426,6 +426,32 @@ def test_sixteen_bit_matrices(shape, fmt):
         kvq.kvq_quantize_t(7, xd, scales, codes, batch, N, D)
 
 
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+def test_sixteen_bit_quantize_every_finite_input_against_many_scales(fmt):
+    """The 16-bit quantize kernel forms x / scale as a product with an fp64 reciprocal (provably the same
+    fp32 quotient).  Every finite fp16 / bf16 value against 1024 scales spread over the whole fp32 range --
+    subnormal, tiny, huge, negative, zero, powers of two and their neighbours -- must give the oracle's
+    codes, which come from the plain fp32 divide."""
+    rng = np.random.default_rng(len(fmt))
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    expo = ((bits >> 10) & 31) if fmt == "f16" else ((bits >> 7) & 255)
+    bits = bits[expo != (31 if fmt == "f16" else 255)]                        # finite values only
+    N, D = bits.size, 1024
+    s = (2.0 ** rng.uniform(-149, 127, D) * rng.uniform(1, 2, D)).astype(np.float32)
+    s[:16] = [0.0, -0.25, 2.0 ** -149, 2.0 ** -140, 2.0 ** -126, 2.0 ** 127, 3.0e38, 1.0, 1.0 + 2.0 ** -23,
+              1.0 - 2.0 ** -24, 1.0 / 127, 3.0, 1.0 / 3, 65504.0 / 127, 2.0 ** -24, 2.0 ** -14 / 127]
+    s[16:272] = (np.abs(oracle.widen16(bits, fmt)[rng.integers(0, N, 256)]) / np.float32(127)).astype(np.float32)
+    s[272:400] *= np.float32(-1)
+    x16 = np.ascontiguousarray(np.broadcast_to(bits[:, None], (N, D)))
+    q_ref = oracle.quantize(oracle.widen16(x16, fmt), s)
+    dt = kvq.DTYPE_F16 if fmt == "f16" else kvq.DTYPE_BF16
+    xd = torch.from_numpy(x16.view(np.int16).reshape(-1)).cuda()
+    sd = torch.from_numpy(s).cuda()
+    codes = torch.full((N * D,), 99, dtype=torch.int8, device="cuda")
+    kvq.kvq_quantize_t(dt, xd, sd, codes, 1, N, D)
+    assert_bits_equal(codes.cpu().numpy().reshape(N, D), q_ref, "%s codes, all inputs x 1024 scales" % fmt)
+
+
 def test_typed_calls_forward_fp32():
     x = W.generate(1)[0]
     g = Gpu(x)
