@@ -133,10 +133,14 @@ __global__ __launch_bounds__(kBlock) void append_merge_kernel(float* __restrict_
 }
 
 // ---- cached rows of grown channels ----
-__device__ __forceinline__ uint32_t requant_byte(uint32_t word, int b, float s_old, float div_new) {
+// The divide is the divide-free quotient of quotient_by (same bits): with the IEEE sequence this pass is
+// bound by the vector ALUs when many channels grow.
+__device__ __forceinline__ uint32_t requant_byte(uint32_t word, int b, float s_old, double rcp_new) {
   const int q = (int)(word << (24 - 8 * b)) >> 24;
   const float xh = (float)q * s_old;  // the reconstruction, rounded to fp32 before the divide
-  return code_bits(xh, div_new) << (8 * b);
+  float y = quotient_by(xh, rcp_new);
+  y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
+  return (__float_as_uint(y + kRoundMagic) & 0xffu) << (8 * b);
 }
 
 template <int V, int U>
@@ -165,6 +169,9 @@ __global__ __launch_bounds__(kBlock) void append_requant_kernel(int8_t* __restri
   int64_t row = it.row0 + it.ty;
   int8_t* pc = codes + (it.slab * capacity + row) * D + col;
   if constexpr (V == 4) {
+    double rn[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) rn[i] = reciprocal_of(dn[i]);
     uint32_t keep = 0;  // byte mask of the channels that stay as they are
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -178,7 +185,7 @@ __global__ __launch_bounds__(kBlock) void append_requant_kernel(int8_t* __restri
       for (int u = 0; u < R; u++) {
         uint32_t r = 0;
 #pragma unroll
-        for (int i = 0; i < 4; i++) r |= requant_byte(w[u], i, so[i], dn[i]);
+        for (int i = 0; i < 4; i++) r |= requant_byte(w[u], i, so[i], rn[i]);
         *reinterpret_cast<uint32_t*>(pc + u * step) = (w[u] & keep) | (r & ~keep);
       }
     };

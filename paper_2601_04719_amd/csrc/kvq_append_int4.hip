@@ -128,6 +128,9 @@ __global__ __launch_bounds__(kBlock) void append4_requant_kernel(uint8_t* __rest
     dn[i] = divisor_of(sn);
   }
   if (!any) return;  // no barrier below: lanes leave independently
+  double rn[V];  // the divide below as the divide-free quotient of quotient_by (same bits)
+#pragma unroll
+  for (int i = 0; i < V; i++) rn[i] = reciprocal_of(dn[i]);
   const int64_t pstep = ((int64_t)it.TY * D) >> 1;  // packed bytes between the rows a lane visits
   int64_t row = it.row0 + it.ty;
   uint8_t* pc = packed + (((it.slab * capacity + row) * D + col) >> 1);
@@ -143,7 +146,9 @@ __global__ __launch_bounds__(kBlock) void append4_requant_kernel(uint8_t* __rest
       for (int i = 0; i < V; i++) {
         const int q = (int)(w[u] << (28 - 4 * i)) >> 28;
         const float xh = (float)q * so[i];  // the reconstruction, rounded to fp32 before the divide
-        r |= nibble_of(xh, dn[i]) << (4 * i);
+        float y = quotient_by(xh, rn[i]);
+        y = __builtin_amdgcn_fmed3f(y, -7.0f, 7.0f);
+        r |= (__float_as_uint(y + kRoundMagic) & 15u) << (4 * i);
       }
       store_codes<V>(pc + u * pstep, (w[u] & keep) | (r & ~keep));
     }

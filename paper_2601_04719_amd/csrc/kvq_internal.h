@@ -246,6 +246,29 @@ constexpr float kRoundMagic = 12582912.0f;
 // Divisor for a channel: its scale, or +inf for a zero scale (x / inf = +-0 -> code 0).
 __device__ __forceinline__ float divisor_of(float s) { return s == 0.0f ? __builtin_inff() : s; }
 
+// The fp32 quotient x / div without the divide.  r approximates 1 / div to within 2^-50 relative (fp64), so
+// (double)x * r is within 2^-26 fp32-ulps of x / div.  A quotient of two fp32 numbers is never
+// closer than 2^-25 ulp to a midpoint between two adjacent fp32 numbers (write x = A 2^a, div = B 2^b
+// with 24-bit integers A, B and a midpoint as M 2^m with M odd: x/div - M 2^m = (A 2^a - B M 2^(b+m)) /
+// (B 2^b) has a nonzero integer multiple of a power of two on top and B < 2^24 below; it cannot be 0
+// because B M has an odd factor beyond 24 bits), in the subnormal and overflow ranges as well, so
+// rounding the product to fp32 gives exactly the correctly rounded fp32 quotient: the same bits as
+// x / div, with 3 instructions per element instead of the 11-12 of the IEEE divide sequence.  Used
+// where a kernel is bound by the vector ALUs rather than by HBM.
+__device__ __forceinline__ float quotient_by(float x, double r) { return (float)((double)x * r); }
+
+// 1 / div in fp64 to within a few 2^-53: hardware estimate, three Newton steps (each squares the
+// relative error, so even a 7-bit estimate would do; one rounding per fma).  div = +-inf (the divisor of a zero scale) gives 0, as x / inf.
+__device__ __forceinline__ double reciprocal_of(float div) {
+  const double d = (double)div;
+  double r = __builtin_amdgcn_rcp(d);
+  r = fma(fma(-d, r, 1.0), r, r);
+  r = fma(fma(-d, r, 1.0), r, r);
+  r = fma(fma(-d, r, 1.0), r, r);
+  return __builtin_isinf(div) ? 0.0 : r;
+}
+
+
 // Decomposition of a work-item index into (slab, row chunk, column tile).
 struct Item {
   int64_t slab;

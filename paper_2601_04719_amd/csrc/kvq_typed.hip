@@ -27,30 +27,12 @@ __device__ __forceinline__ uint32_t code_byte(float x, float div) {
   return __float_as_uint(y + kRoundMagic) & 0xffu;
 }
 
-// The same quotient without the divide.  r approximates 1 / div to within 2^-50 relative (fp64), so
-// (double)x * r is within 2^-26 fp32-ulps of x / div.  A quotient of two fp32 numbers is never
-// closer than 2^-25 ulp to a midpoint between two adjacent fp32 numbers (write x = A 2^a, div = B 2^b
-// with 24-bit integers A, B and a midpoint as M 2^m with M odd: x/div - M 2^m = (A 2^a - B M 2^(b+m)) /
-// (B 2^b) has a nonzero integer multiple of a power of two on top and B < 2^24 below; it cannot be 0
-// because B M has an odd factor beyond 24 bits), in the subnormal and overflow ranges as well, so
-// rounding the product to fp32 gives exactly the correctly rounded fp32 quotient: the same bits as
-// x / div, with 3 instructions per element instead of the 11-12 of the IEEE divide sequence.  The
-// 16-bit quantize kernel is bound by the vector ALUs, not by HBM; this is what it runs.
+// int8 code of x by the divide-free quotient (see quotient_by): what the vector kernel runs, because with
+// the divide sequence it was bound by the vector ALUs, not by HBM
 __device__ __forceinline__ uint32_t code_byte_r(float x, double r) {
-  float y = (float)((double)x * r);
+  float y = quotient_by(x, r);
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
   return __float_as_uint(y + kRoundMagic) & 0xffu;
-}
-
-// 1 / div in fp64 to within a few 2^-53: hardware estimate, three Newton steps (each squares the
-// relative error, so even a 7-bit estimate would do; one rounding per fma).  div = +-inf (the divisor of a zero scale) gives 0, as x / inf.
-__device__ __forceinline__ double reciprocal_of(float div) {
-  const double d = (double)div;
-  double r = __builtin_amdgcn_rcp(d);
-  r = fma(fma(-d, r, 1.0), r, r);
-  r = fma(fma(-d, r, 1.0), r, r);
-  r = fma(fma(-d, r, 1.0), r, r);
-  return __builtin_isinf(div) ? 0.0 : r;
 }
 
 // ---- absmax --------------------------------------------------------------------------------
