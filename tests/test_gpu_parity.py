@@ -1006,6 +1006,44 @@ def test_streaming_append_onto_a_four_bit_cache(shape, chunks, offset):
     assert e.value.status == kvq.ERR_ARG
 
 
+def test_append_requantization_on_and_next_to_ties():
+    """The requantization forms (float)code * s_old / s_new without a divide instruction.  Every code value
+    in every channel, with new scales that are 2 s_old up to a rounding error (quotients on and within an ulp
+    of .5 ties), a little above s_old (quotients just under the integers) and far above: the oracle, which
+    divides in fp32, must be matched bit for bit -- for the 8-bit and the 4-bit cache."""
+    rng = np.random.default_rng(77)
+    D = 512
+    for qmax, fn in ((127, "int8"), (7, "int4")):
+        n_old = 2 * qmax + 1
+        cap = n_old + 1
+        s_old = np.exp(rng.uniform(-20, 20, (1, D))).astype(np.float32)
+        cache = np.zeros((1, cap, D), dtype=np.int8)
+        cache[0, :n_old] = np.arange(-qmax, qmax + 1, dtype=np.int8)[:, None]
+        tok = np.zeros((1, 1, D), dtype=np.float32)
+        third = D // 3
+        tok[0, 0, :third] = (s_old[0, :third] * np.float32(2 * qmax)) * rng.choice([-1, 1], third).astype(np.float32)
+        tok[0, 0, :third] *= 1 + rng.integers(0, 4, third).astype(np.float32) * np.float32(2.0 ** -23)   # s_new = 2 s_old (1 + k ulp)
+        tok[0, 0, third:2 * third] = s_old[0, third:2 * third] * np.float32(qmax) * (
+            1 + rng.integers(1, 64, third).astype(np.float32) * np.float32(2.0 ** -22))
+        tok[0, 0, 2 * third:] = s_old[0, 2 * third:] * np.float32(qmax) * np.exp(rng.uniform(0, 8, D - 2 * third)).astype(np.float32)
+        ref_codes, ref_scales, _ = oracle.append_q(cache, s_old, n_old, tok, qmax)
+        assert (ref_scales > s_old).all()
+        scales = torch.from_numpy(s_old.reshape(-1)).cuda()
+        prev = torch.empty_like(scales)
+        xs = torch.from_numpy(tok.reshape(-1)).cuda()
+        if qmax == 127:
+            codes = torch.from_numpy(cache.reshape(-1)).cuda()
+            kvq.kvq_append(xs, scales, prev, codes, 1, n_old, 1, cap, D)
+            got = codes.cpu().numpy().reshape(1, cap, D)
+            assert_bits_equal(got, ref_codes, "8-bit cache")
+        else:
+            packed = torch.from_numpy(oracle.pack_int4(cache).reshape(-1)).cuda()
+            kvq.kvq_append_int4(xs, scales, prev, packed, 1, n_old, 1, cap, D)
+            got = packed.cpu().numpy().reshape(1, cap, D // 2)
+            assert np.array_equal(got, oracle.pack_int4(ref_codes)), "4-bit cache"
+        assert_bits_equal(scales.cpu().numpy().reshape(1, D), ref_scales, fn + " scales")
+
+
 def test_streaming_append_argument_errors():
     g = GpuCache(1, 8, 4)
     x = torch.zeros(4 * 4, dtype=torch.float32, device="cuda")
