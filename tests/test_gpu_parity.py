@@ -442,6 +442,9 @@ def test_sixteen_bit_quantize_every_finite_input_against_many_scales(fmt):
               1.0 - 2.0 ** -24, 1.0 / 127, 3.0, 1.0 / 3, 65504.0 / 127, 2.0 ** -24, 2.0 ** -14 / 127]
     s[16:272] = (np.abs(oracle.widen16(bits, fmt)[rng.integers(0, N, 256)]) / np.float32(127)).astype(np.float32)
     s[272:400] *= np.float32(-1)
+    # scales that put some input within an ulp of a .5 tie: |x0| / (k + 0.5)
+    x0 = np.abs(oracle.widen16(bits, fmt)[rng.integers(0, N, 512)])
+    s[400:912] = (x0 / (rng.integers(0, 127, 512).astype(np.float32) + np.float32(0.5))).astype(np.float32)
     x16 = np.ascontiguousarray(np.broadcast_to(bits[:, None], (N, D)))
     q_ref = oracle.quantize(oracle.widen16(x16, fmt), s)
     dt = kvq.DTYPE_F16 if fmt == "f16" else kvq.DTYPE_BF16
