@@ -28,6 +28,15 @@ def test_header_and_binding_list_the_same_entry_points():
         assert callable(getattr(kvq, n)), n
 
 
+def test_header_and_binding_agree_on_every_constant():
+    text = open(HEADER).read()
+    defines = dict(re.findall(r"^#define KVQ_([A-Z0-9_]+)\s+\(?(-?\d+)\)?", text, flags=re.M))
+    assert len(defines) >= 25
+    for name, value in defines.items():
+        assert hasattr(kvq, name), "kvq.py lacks %s" % name
+        assert getattr(kvq, name) == int(value), name
+
+
 def test_library_exports_every_declared_symbol():
     L = kvq.lib()
     for n in declared_functions():
