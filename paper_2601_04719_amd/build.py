@@ -4,20 +4,28 @@ The flags pin the numerics the parity tests rely on: no FMA contraction (the
 round-trip error recomputes (float)code*scale and subtracts it in two steps),
 correctly rounded fp32 divide, no denormal flushing, and no packed-fp32
 instructions.
+
+Every source becomes one object under _build/ (compiled in parallel), then the
+objects are linked.  `python -m paper_2601_04719_amd.build` recompiles
+everything; `--incremental` skips objects newer than their source and every
+header.
 """
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libkvq.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
+HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h")))
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off", "-fno-fast-math",
     "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-gpu-flush-denormals-to-zero",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -26,15 +34,38 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra=()) -> str:
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-o", tmp] + SOURCES
+def _compile(src, obj, extra, verbose):
+    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", "-o", obj, src]
     if verbose:
-        print(" ".join(cmd))
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+
+
+def build(verbose: bool = False, extra=(), incremental: bool = False) -> str:
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    newest_header = max(os.path.getmtime(h) for h in HEADERS)
+    jobs, objects = [], []
+    for src in SOURCES:
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        objects.append(obj)
+        fresh = (incremental and not extra and os.path.exists(obj)
+                 and os.path.getmtime(obj) >= max(os.path.getmtime(src), newest_header))
+        if not fresh:
+            jobs.append((src, obj))
+    workers = max(1, min(len(jobs), os.cpu_count() or 1, 16))
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        for f in [pool.submit(_compile, s, o, extra, verbose) for s, o in jobs]:
+            f.result()
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objects
+    if verbose:
+        print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIB)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, extra=sys.argv[1:]))
+    args = sys.argv[1:]
+    inc = "--incremental" in args
+    print(build(verbose=True, extra=[a for a in args if a != "--incremental"], incremental=inc))
