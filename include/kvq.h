@@ -49,6 +49,7 @@ typedef int kvq_status;
 #define KVQ_ERR_OVERFLOW (-3) /* batch*N*D (or a launch dimension) exceeds what is indexable */
 #define KVQ_ERR_HIP (-4)      /* a HIP runtime call failed; see kvq_last_hip_error()      */
 #define KVQ_ERR_ARG (-5)      /* inconsistent optional arguments                          */
+#define KVQ_ERR_LIMIT (-6)    /* larger than the fixed scratch of an entry point that allocates nothing */
 
 /* Same type as hipStream_t (an opaque pointer); declared here so that callers
  * need no HIP headers. */
@@ -64,6 +65,26 @@ typedef struct ihipStream_t *kvq_stream_t;
  */
 kvq_status kvq_absmax_scales(const float *x, float *scales,
                              int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
+
+/*
+ * kvq_absmax_scales for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same bits
+ * as kvq_absmax_scales, but the partial maxima of a reduction split over row chunks go to a fixed
+ * array inside the library's device image instead of the per-stream workspace, so this call never
+ * calls hipMalloc / hipFree (nor any allocating library routine), on its first use either.
+ *   limit: batch * D <= KVQ_STATIC_SCRATCH_FLOATS channels (one slot per channel and row chunk;
+ *          8 MiB of device memory that every GPU the library runs on holds until the process
+ *          ends).  Beyond it: KVQ_ERR_LIMIT, nothing enqueued.  Within it, fewer slots only mean
+ *          fewer, longer row chunks.
+ *   sharing: all calls on one GPU use that GPU's one array, whatever their stream.  Calls on the
+ *          same stream are ordered by it; calls in flight at the same time on different streams
+ *          of one GPU race on the array and give undefined scales.  The array keeps the last
+ *          call's contents; nothing in it needs clearing, because each call writes every slot it
+ *          later reads.
+ */
+#define KVQ_STATIC_SCRATCH_FLOATS 2097152
+kvq_status kvq_absmax_scales_static(const float *x, float *scales,
+                                    int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);
 
 /*
  * Quantization -- Eq. (quantize)/(quant_op) plus the stated clamp:

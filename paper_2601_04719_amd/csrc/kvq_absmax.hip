@@ -21,6 +21,7 @@
 // the 1B-element shape: 7.0 TB/s, against 6.5 TB/s with eight 4 KiB-wide
 // workgroups per compute unit, and 4 TB/s for one-shot workgroups of a few rows
 // (measured when every workgroup still ended in an atomic per channel).
+#include <mutex>
 #include <type_traits>
 
 #include "kvq_internal.h"
@@ -173,7 +174,8 @@ static kvq_status launch_absmax_t(const float* x, float* dst, int64_t chunk_stri
   return KVQ_OK;
 }
 
-kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, int* J_out, int* U_out, Tiling* t_out) {
+kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, int* J_out, int* U_out, Tiling* t_out,
+                       int64_t colmax_floats) {
   const Options& o = options();
   const int V = vec ? 4 : 1;
   // J column groups per lane: as many as it takes for a workgroup to span whole rows, at most 8.
@@ -206,7 +208,7 @@ kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, i
     t.ctiles = (uint32_t)((t.groups + (int64_t)kBlock * J - 1) / ((int64_t)kBlock * J));
     t.items = batch * (int64_t)t.rchunks * t.ctiles;
   }
-  limit_row_chunks(&t, batch, N, absmax_chunk_cap(batch * D));
+  limit_row_chunks(&t, batch, N, colmax_floats / (batch * D));
   if (t.items > INT32_MAX) return KVQ_ERR_OVERFLOW;
   *J_out = J;
   *U_out = U;
@@ -215,20 +217,24 @@ kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, i
 }
 
 kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
-                                hipStream_t stream, float qmax) {
+                                hipStream_t stream, float qmax, float* colmax, int64_t colmax_floats) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   const Options& o = options();
   const int V = (D % 4 == 0 && aligned(x, 16)) ? 4 : 1;
   int J, U;
   Tiling t;
-  if (kvq_status s = absmax_plan(dev.cus, batch, N, D, V == 4, &J, &U, &t)) return s;
+  if (colmax == nullptr) colmax_floats = kColmaxFloats;
+  if (kvq_status s = absmax_plan(dev.cus, batch, N, D, V == 4, &J, &U, &t, colmax_floats)) return s;
   const int64_t total = batch * D;
   float* dst = scales;
   if (t.rchunks > 1) {
-    Workspace ws;
-    if (kvq_status s = get_workspace(stream, &ws)) return s;
-    dst = ws.colmax;
+    if (colmax == nullptr) {
+      Workspace ws;
+      if (kvq_status s = get_workspace(stream, &ws)) return s;
+      colmax = ws.colmax;
+    }
+    dst = colmax;
   }
   const bool nt = o.nontemporal != 0;
   kvq_status s;
@@ -258,6 +264,35 @@ kvq_status launch_absmax_finalize(const float* colmax, float* scales, int64_t to
   return KVQ_OK;
 }
 
+// ------------------------------------------------------------ the scale reduction without an allocation
+// For callers that cannot allocate (code under HIP graph capture, serving loops, harnesses that forbid
+// it): the per-row-chunk maxima go to a fixed array in device memory instead of the per-stream workspace.
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name only stands for the symbol; the address kernels can use is asked
+// from the runtime once per device and kept.
+static __device__ __align__(256) float scratch[KVQ_STATIC_SCRATCH_FLOATS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices];  // per device: device address of `scratch`, null until asked
+
+kvq_status static_scratch(float** out) {
+  int dev = -1;
+  KVQ_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return hip_failed(hipErrorInvalidDevice);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    KVQ_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return hip_failed(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return KVQ_OK;
+}
+}  // namespace
+
 void limit_row_chunks(Tiling* t, int64_t batch, int64_t N, int64_t cap) {
   if (cap < 1) cap = 1;
   if ((int64_t)t->rchunks <= cap) return;
@@ -269,3 +304,19 @@ void limit_row_chunks(Tiling* t, int64_t batch, int64_t N, int64_t cap) {
 }
 
 }  // namespace kvq
+
+// The entry point lives in this file, next to the array, the look-up of its address and the kernels
+// that take that address as an argument.
+extern "C" kvq_status kvq_absmax_scales_static(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
+                                               kvq_stream_t stream) {
+  using namespace kvq;
+  if (!x || !scales) return KVQ_ERR_NULL;
+  if (kvq_status s = check_shape(batch, N, D)) return s;
+  // every (slab, channel) needs one slot per row chunk
+  if (batch * D > (int64_t)KVQ_STATIC_SCRATCH_FLOATS) return KVQ_ERR_LIMIT;
+  float* ptr = nullptr;
+  if (kvq_status s = static_scratch(&ptr)) return s;
+  // Nothing in the array has to start at zero: every workgroup of the first stage stores the maxima of
+  // all channels of its (row chunk, slab, column tile), and the second stage reads exactly those slots.
+  return launch_absmax_scales(x, scales, batch, N, D, stream, 127.0f, ptr, (int64_t)KVQ_STATIC_SCRATCH_FLOATS);
+}

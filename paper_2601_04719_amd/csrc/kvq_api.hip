@@ -24,14 +24,15 @@ Options& options() {
 }
 
 DeviceInfo current_device() {
+  // a fixed table, so that a call never allocates host memory either
+  constexpr int kMaxDevices = 64;
   static std::mutex mu;
-  static std::map<int, DeviceInfo> cache;
+  static DeviceInfo cache[kMaxDevices];
   DeviceInfo info;
   int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess) return info;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return info;
   std::lock_guard<std::mutex> lock(mu);
-  auto it = cache.find(dev);
-  if (it != cache.end()) return it->second;
+  if (cache[dev].cus > 0) return cache[dev];
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
     return info;
@@ -158,7 +159,7 @@ kvq_status release_workspace(hipStream_t stream) {
 }
 
 // batch, N, D >= 1 and batch*N*D (in bytes of fp32) indexable in int64 / size_t.
-static kvq_status check_shape(int64_t batch, int64_t N, int64_t D) {
+kvq_status check_shape(int64_t batch, int64_t N, int64_t D) {
   if (batch < 1 || N < 1 || D < 1) return KVQ_ERR_SHAPE;
   const int64_t lim = INT64_MAX / 8;  // room for the 4-byte element size and headroom
   if (N > lim / D) return KVQ_ERR_OVERFLOW;
@@ -415,6 +416,7 @@ const char* kvq_status_string(kvq_status status) {
     case KVQ_ERR_OVERFLOW: return "KVQ_ERR_OVERFLOW: problem size is not indexable";
     case KVQ_ERR_HIP: return "KVQ_ERR_HIP: a HIP runtime call failed";
     case KVQ_ERR_ARG: return "KVQ_ERR_ARG: inconsistent or out-of-range argument";
+    case KVQ_ERR_LIMIT: return "KVQ_ERR_LIMIT: problem exceeds the fixed scratch of an entry point that allocates nothing";
     default: return "unknown kvq status";
   }
 }

@@ -52,7 +52,9 @@ kvq_status stream_tiling_for(int cus, int64_t batch, int64_t N, int64_t D, int V
                              int default_passes = 1);
 // Launch shape of the fp32 scale reduction: J column groups per lane, U rows in flight, tiling in units of
 // J * V channels per lane, row chunks limited to what the workspace holds.  vec = 16-byte row access.
-kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, int* J_out, int* U_out, Tiling* t_out);
+// colmax_floats = size of the buffer that takes the per-row-chunk maxima.
+kvq_status absmax_plan(int cus, int64_t batch, int64_t N, int64_t D, bool vec, int* J_out, int* U_out, Tiling* t_out,
+                       int64_t colmax_floats = (int64_t)1 << 22);
 
 // default launch shapes of the fp32 codec kernels: rows in flight per lane, threads per workgroup
 constexpr int kQuantUnroll = 4, kQuantBlock = 512, kDequantUnroll = 2, kDequantBlock = 256;
@@ -87,6 +89,9 @@ kvq_status hip_failed(hipError_t e);
     if (kvq_e_ != hipSuccess) return hip_failed(kvq_e_); \
   } while (0)
 
+// batch, N, D >= 1 and batch * N * D elements indexable: KVQ_OK, KVQ_ERR_SHAPE or KVQ_ERR_OVERFLOW
+kvq_status check_shape(int64_t batch, int64_t N, int64_t D);
+
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Largest lane width V in {16, 8, 4} (capped by `want`) such that rows of D fp32
@@ -108,8 +113,11 @@ kvq_status release_workspace(hipStream_t stream);
 
 // ---- launchers (each validates nothing: the C-ABI layer has done that) ----
 // scales = column absmax / qmax (127 for 8-bit codes, 7 for 4-bit codes)
+// colmax = where the per-row-chunk maxima go, [row chunk][batch * D] within colmax_floats floats;
+// nullptr = the stream's workspace (allocated on first use)
 kvq_status launch_absmax_scales(const float* x, float* scales, int64_t batch, int64_t N, int64_t D,
-                                hipStream_t stream, float qmax = 127.0f);
+                                hipStream_t stream, float qmax = 127.0f, float* colmax = nullptr,
+                                int64_t colmax_floats = 0);
 // second stage of a scale reduction that was split over row chunks:
 // scales[i] = max_r colmax[r * total + i] / qmax
 kvq_status launch_absmax_finalize(const float* colmax, float* scales, int64_t total, uint32_t rchunks, float qmax,

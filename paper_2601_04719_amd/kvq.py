@@ -14,14 +14,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvq.so")
 
 OK = 0
-ERR_NULL, ERR_SHAPE, ERR_OVERFLOW, ERR_HIP, ERR_ARG = -1, -2, -3, -4, -5
+ERR_NULL, ERR_SHAPE, ERR_OVERFLOW, ERR_HIP, ERR_ARG, ERR_LIMIT = -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_FLOATS = 2097152
 OPT_CODEC_WIDTH, OPT_CODEC_UNROLL, OPT_BLOCKS_PER_CU, OPT_NONTEMPORAL = 1, 2, 3, 4
 OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES, OPT_ABSMAX_SPAN = 6, 7, 8, 9, 10
 OPT_ABSMAX_BLOCKS_PER_CU = 11
 OPT_APPEND_BLOCKS_PER_CU = 12
 
 EXPORTS = (
-    "kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused", "kvq_quantize_variant",
+    "kvq_absmax_scales", "kvq_absmax_scales_static", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
+    "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
     "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_append_int4", "kvq_plan", "kvq_prepare_stream", "kvq_release_stream",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
@@ -51,6 +53,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.kvq_absmax_scales.argtypes = [p, p, i64, i64, i64, p]
+        L.kvq_absmax_scales_static.argtypes = [p, p, i64, i64, i64, p]
+        L.kvq_absmax_scales_static.restype = i32
         L.kvq_quantize.argtypes = [p, p, p, i64, i64, i64, p]
         L.kvq_dequantize.argtypes = [p, p, p, i64, i64, i64, p]
         L.kvq_quantize_fused.argtypes = [p, p, p, i64, i64, i64, p]
@@ -133,6 +137,11 @@ def _check(status, where):
 
 def kvq_absmax_scales(x, scales, batch, N, D, stream=None):
     _check(lib().kvq_absmax_scales(_addr(x), _addr(scales), batch, N, D, _stream(stream)), "kvq_absmax_scales")
+
+
+def kvq_absmax_scales_static(x, scales, batch, N, D, stream=None):
+    _check(lib().kvq_absmax_scales_static(_addr(x), _addr(scales), batch, N, D, _stream(stream)),
+           "kvq_absmax_scales_static")
 
 
 def kvq_quantize(x, scales, codes, batch, N, D, stream=None):

@@ -45,7 +45,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert kvq.kvq_status_string(0) == "KVQ_OK"
-    for s in (-1, -2, -3, -4, -5):
+    for s in (-1, -2, -3, -4, -5, -6):
         assert kvq.kvq_status_string(s).startswith("KVQ_ERR_")
     assert "unknown" in kvq.kvq_status_string(-99)
 
@@ -74,6 +74,11 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.kvq_attn_score_error(fake, 0, fake, fake, None, None, 4, 4, fake, None) == kvq.ERR_SHAPE
     assert L.kvq_attn_score_error(fake, 2, fake, None, None, None, 4, 4, fake, None) == kvq.ERR_NULL
     assert L.kvq_attn_score_error(None, 2, fake, fake, None, None, 4, 4, fake, None) == kvq.ERR_NULL
+    # the entry point that allocates nothing: argument errors as elsewhere, and its size limit
+    assert L.kvq_absmax_scales_static(None, fake, 1, 4, 4, None) == kvq.ERR_NULL
+    assert L.kvq_absmax_scales_static(fake, fake, 1, 0, 4, None) == kvq.ERR_SHAPE
+    assert L.kvq_absmax_scales_static(fake, fake, 1, 4, kvq.STATIC_SCRATCH_FLOATS + 1, None) == kvq.ERR_LIMIT
+    assert L.kvq_absmax_scales_static(fake, fake, kvq.STATIC_SCRATCH_FLOATS // 64 + 1, 4, 64, None) == kvq.ERR_LIMIT
     with pytest.raises(kvq.KvqError) as e:
         kvq.kvq_quantize(fake, fake, fake, 1, 0, 4)
     assert e.value.status == kvq.ERR_SHAPE and "KVQ_ERR_SHAPE" in str(e.value)
