@@ -1,11 +1,7 @@
-// Error statistics of the round trip
-// (paper: Introduction, "Reconstruction error" and "Attention score error";
-//  Evaluation, "Reconstruction Error" and "Attention Score Error").
-//
-//  - reconstruction error: sum of squares of the fp32 difference x - x_hat,
-//    squared and summed in fp64, and the largest |x - x_hat|.
-//  - attention-score error: mean over (query, token) of |q.k - q.k_hat|,
-//    computed as |sum_d q_d (k_d - k_hat_d)| in fp64 on the fp64 matrix cores.
+// Reconstruction error of the round trip
+// (paper: Introduction, "Reconstruction error"; Evaluation, "Reconstruction Error"):
+// sum of squares of the fp32 difference x - x_hat, squared and summed in fp64, and
+// the largest |x - x_hat|.
 //
 // Reductions are two-level and order-fixed: every workgroup writes one partial
 // (sum, max) into a per-stream workspace, and a single-workgroup kernel folds
@@ -13,41 +9,9 @@
 #include <type_traits>
 
 #include "kvq_internal.h"
+#include "kvq_reduce.h"
 
 namespace kvq {
-
-// ---------------------------------------------------------------- reductions
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_down(v, off, 64));
-  return v;
-}
-
-// Workgroup-wide (sum, max); the result is valid in thread 0.
-__device__ __forceinline__ void block_reduce(double& sum, float& mx) {
-  __shared__ double s_sum[kBlock / 64];
-  __shared__ float s_max[kBlock / 64];
-  sum = wave_sum(sum);
-  mx = wave_max(mx);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (lane == 0) {
-    s_sum[wave] = sum;
-    s_max[wave] = mx;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-#pragma unroll
-    for (int w = 1; w < kBlock / 64; w++) {
-      sum += s_sum[w];
-      mx = fmaxf(mx, s_max[w]);
-    }
-  }
-}
 
 // Folds n partials in index order.  sum_out = sum * sum_scale; max_out may be NULL.
 __global__ __launch_bounds__(kBlock) void fold_partials(const double* __restrict__ sums,
@@ -379,237 +343,9 @@ kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, con
   return KVQ_OK;
 }
 
-// ------------------------------------------------------ attention-score error
-// The score difference  q_j . k_t - q_j . k_hat_t = sum_d q_j[d] (k_t[d] - k_hat_t[d])  is a dense
-// [tokens x D] . [D x queries] contraction in fp64, so it runs on the fp64 matrix cores
-// (v_mfma_f64_16x16x4_f64).
-//
-// A workgroup (4 wavefronts) owns 64 tokens x 16*NQ queries and walks D in chunks of kDc channels.
-// Per chunk it stages e = (double)k - (double)k_hat [64 x kDc] and the queries [16*NQ x kDc] in LDS
-// as fp64 (converted once, with 256-byte coalesced global reads), double-buffered: the global loads
-// of chunk c+1 are in flight while chunk c is contracted, one barrier per chunk.  Wavefront w owns
-// tokens 16w..16w+15 and NQ accumulator tiles.  For each block of 16 channels, lane (r = lane % 16,
-// g = lane / 16) reads channels 4g..4g+3 of token r and of query r of every query tile from LDS and
-// feeds four MFMA steps; step c contracts channels {4g + c : g = 0..3}.  Only sum |C| over the
-// accumulator tiles is needed, so where C elements sit in registers does not matter.  Tokens,
-// queries and channels outside the matrices are staged as zeros and add |0|.
-typedef double f64x4 __attribute__((ext_vector_type(4)));
-typedef double f64x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kTok = 64;  // tokens per workgroup
-
-struct Quad {
-  float v[4];
-};
-
-// four consecutive floats p[idx..idx+3] of a row (vector load when VEC), zero where idx + i >= limit or !ok
-template <bool VEC>
-__device__ __forceinline__ Quad load_quad(const float* __restrict__ row, int64_t idx, int64_t limit, bool ok) {
-  Quad q;
-  if constexpr (VEC) {
-    f32x4 t = {0.f, 0.f, 0.f, 0.f};
-    if (ok && idx < limit) t = *reinterpret_cast<const f32x4*>(row + idx);
-    q.v[0] = t.x; q.v[1] = t.y; q.v[2] = t.z; q.v[3] = t.w;
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; i++) q.v[i] = (ok && idx + i < limit) ? row[idx + i] : 0.0f;
-  }
-  return q;
-}
-
-// same for the reconstructed key: either read, or recomputed as (float)code * scale
-template <bool VEC, bool FROM_CODES>
-__device__ __forceinline__ Quad load_khat(const float* __restrict__ k_hat, const int8_t* __restrict__ codes,
-                                          const float* __restrict__ scales, int64_t row_off, int64_t d, int64_t D,
-                                          bool ok) {
-  if constexpr (!FROM_CODES) {
-    return load_quad<VEC>(k_hat + row_off, d, D, ok);
-  } else {
-    Quad q;
-    if constexpr (VEC) {
-      uint32_t w = 0;
-      f32x4 s = {0.f, 0.f, 0.f, 0.f};
-      if (ok && d < D) {
-        w = *reinterpret_cast<const uint32_t*>(codes + row_off + d);
-        s = *reinterpret_cast<const f32x4*>(scales + d);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; i++) q.v[i] = (float)((int)(w << (24 - 8 * i)) >> 24) * s[i];
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-        q.v[i] = (ok && d + i < D) ? (float)codes[row_off + d + i] * scales[d + i] : 0.0f;
-    }
-    return q;
-  }
-}
-
-// kDc = channels per staged chunk: 32 lets two workgroups share a compute unit's LDS (they overlap each
-// other's staging); 64 halves the barriers and is the better choice when there is at most one
-// workgroup per compute unit anyway.
-template <int NQ, int kDc, bool VEC, bool FROM_CODES>
-__global__ __launch_bounds__(kBlock) void attn_score_kernel(const float* __restrict__ queries, int64_t Q,
-                                                            const float* __restrict__ k,
-                                                            const float* __restrict__ k_hat,
-                                                            const int8_t* __restrict__ codes,
-                                                            const float* __restrict__ scales, int64_t N,
-                                                            int64_t D, uint32_t qchunks, uint32_t tiles,
-                                                            double* __restrict__ sums) {
-  constexpr int kPitch = kDc + 2;                // LDS row pitch in doubles: 16-byte skew between rows
-  constexpr int QR = 16 * NQ;                    // query rows staged per chunk
-  constexpr int F4 = kDc / 4;                    // 16-byte pieces per staged row
-  constexpr int ROWS_PER_PASS = kBlock / F4;     // rows one fill pass of the workgroup covers
-  constexpr int KP = kTok / ROWS_PER_PASS;       // fill passes for the token rows
-  constexpr int QP = (QR + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
-  __shared__ double e_s[2][kTok][kPitch];
-  __shared__ double q_s[2][QR][kPitch];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 15;   // row of the 16-row operand tile: a token (A operand) or a query (B operand)
-  const int g = lane >> 4;   // which 4 of a block's 16 channels this lane supplies
-  const int frow = tid / F4; // fill role: row within a pass, and which 16-byte piece of the chunk
-  const int fcol = (tid % F4) * 4;
-  double total = 0.0;
-
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const int64_t q0 = (int64_t)(tile % qchunks) * QR;
-    const int64_t t0 = (int64_t)(tile / qchunks) * kTok;
-    f64x4 acc[NQ];
-#pragma unroll
-    for (int n = 0; n < NQ; n++) acc[n] = f64x4{0.0, 0.0, 0.0, 0.0};
-
-    Quad kv[KP], hv[KP], qv[QP];
-    auto fetch = [&](int64_t d0) {
-      const int64_t d = d0 + fcol;
-#pragma unroll
-      for (int p = 0; p < KP; p++) {
-        const int64_t tok = t0 + frow + p * ROWS_PER_PASS;
-        kv[p] = load_quad<VEC>(k + tok * D, d, D, tok < N);
-        hv[p] = load_khat<VEC, FROM_CODES>(k_hat, codes, scales, tok * D, d, D, tok < N);
-      }
-#pragma unroll
-      for (int p = 0; p < QP; p++) {
-        const int row = frow + p * ROWS_PER_PASS;
-        const int64_t qi = q0 + row;
-        qv[p] = load_quad<VEC>(queries + qi * D, d, D, row < QR && qi < Q);
-      }
-    };
-    auto stage = [&](int buf) {
-#pragma unroll
-      for (int p = 0; p < KP; p++) {
-        double* dst = &e_s[buf][frow + p * ROWS_PER_PASS][fcol];
-        f64x2 lo = {(double)kv[p].v[0] - (double)hv[p].v[0], (double)kv[p].v[1] - (double)hv[p].v[1]};
-        f64x2 hi = {(double)kv[p].v[2] - (double)hv[p].v[2], (double)kv[p].v[3] - (double)hv[p].v[3]};
-        *reinterpret_cast<f64x2*>(dst) = lo;
-        *reinterpret_cast<f64x2*>(dst + 2) = hi;
-      }
-#pragma unroll
-      for (int p = 0; p < QP; p++) {
-        const int row = frow + p * ROWS_PER_PASS;
-        if (row < QR) {
-          double* dst = &q_s[buf][row][fcol];
-          f64x2 lo = {(double)qv[p].v[0], (double)qv[p].v[1]};
-          f64x2 hi = {(double)qv[p].v[2], (double)qv[p].v[3]};
-          *reinterpret_cast<f64x2*>(dst) = lo;
-          *reinterpret_cast<f64x2*>(dst + 2) = hi;
-        }
-      }
-    };
-
-    __syncthreads();  // the previous tile's last chunk has been consumed by every wavefront
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    int buf = 0;
-    for (int64_t d0 = 0; d0 < D; d0 += kDc, buf ^= 1) {
-      const bool more = d0 + kDc < D;
-      if (more) fetch(d0 + kDc);
-      // operands of block b+1 are read from LDS before the MFMAs of block b are issued
-      double e[4], qd[NQ][4];
-      auto read_block = [&](int b, double (&e_)[4], double (&q_)[NQ][4]) {
-        const double* ep = &e_s[buf][16 * wave + r][16 * b + 4 * g];
-        const f64x2 e01 = *reinterpret_cast<const f64x2*>(ep);
-        const f64x2 e23 = *reinterpret_cast<const f64x2*>(ep + 2);
-        e_[0] = e01.x; e_[1] = e01.y; e_[2] = e23.x; e_[3] = e23.y;
-#pragma unroll
-        for (int n = 0; n < NQ; n++) {
-          const double* qp = &q_s[buf][16 * n + r][16 * b + 4 * g];
-          const f64x2 q01 = *reinterpret_cast<const f64x2*>(qp);
-          const f64x2 q23 = *reinterpret_cast<const f64x2*>(qp + 2);
-          q_[n][0] = q01.x; q_[n][1] = q01.y; q_[n][2] = q23.x; q_[n][3] = q23.y;
-        }
-      };
-      read_block(0, e, qd);
-#pragma unroll
-      for (int b = 0; b < kDc / 16; b++) {
-        double e_n[4], qd_n[NQ][4];
-        if (b + 1 < kDc / 16) read_block(b + 1, e_n, qd_n);
-#pragma unroll
-        for (int c = 0; c < 4; c++)
-#pragma unroll
-          for (int n = 0; n < NQ; n++)
-            acc[n] = __builtin_amdgcn_mfma_f64_16x16x4f64(e[c], qd[n][c], acc[n], 0, 0, 0);
-        if (b + 1 < kDc / 16) {
-#pragma unroll
-          for (int c = 0; c < 4; c++) {
-            e[c] = e_n[c];
-#pragma unroll
-            for (int n = 0; n < NQ; n++) qd[n][c] = qd_n[n][c];
-          }
-        }
-      }
-      if (more) stage(buf ^ 1);
-      __syncthreads();
-    }
-#pragma unroll
-    for (int n = 0; n < NQ; n++)
-#pragma unroll
-      for (int i = 0; i < 4; i++) total += fabs(acc[n][i]);
-  }
-  float unused = 0.0f;
-  block_reduce(total, unused);
-  if (threadIdx.x == 0) sums[blockIdx.x] = total;
-}
-
-kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float* k, const float* k_hat,
-                                   const int8_t* codes, const float* scales, int64_t N, int64_t D,
-                                   double* mean_abs_out, hipStream_t stream) {
-  Workspace ws;
-  if (kvq_status s = get_workspace(stream, &ws)) return s;
-  const int NQ = Q > 32 ? 4 : Q > 16 ? 2 : 1;          // query tiles of 16 per workgroup
-  const int64_t qchunks = (Q + 16 * NQ - 1) / (16 * NQ);
-  const int64_t ttiles = (N + kTok - 1) / kTok;
-  if (qchunks > INT32_MAX / 2 || ttiles > INT32_MAX / qchunks) return KVQ_ERR_OVERFLOW;
-  const int64_t tiles = qchunks * ttiles;
-  const int64_t blocks = tiles < kMaxPartials ? tiles : kMaxPartials;
-  const bool from_codes = k_hat == nullptr;
-  bool vec = D % 4 == 0 && aligned(queries, 16) && aligned(k, 16);
-  vec = vec && (from_codes ? (aligned(codes, 4) && aligned(scales, 16)) : aligned(k_hat, 16));
-  const dim3 grid((uint32_t)blocks), block(kBlock);
-  const DeviceInfo dev = current_device();
-  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
-  const bool wide = tiles <= (int64_t)dev.cus;   // at most one workgroup per compute unit: long chunks
-#define KVQ_LAUNCH_AS(NQ_, DC_, VEC_, FC_)                                                                      \
-  hipLaunchKernelGGL((attn_score_kernel<NQ_, DC_, VEC_, FC_>), grid, block, 0, stream, queries, Q, k, k_hat,    \
-                     codes, scales, N, D, (uint32_t)qchunks, (uint32_t)tiles, ws.sums)
-#define KVQ_PICK_AS(NQ_)                                                 \
-  do {                                                                   \
-    if (vec && from_codes && wide) KVQ_LAUNCH_AS(NQ_, 64, true, true);   \
-    else if (vec && from_codes) KVQ_LAUNCH_AS(NQ_, 32, true, true);      \
-    else if (vec && wide) KVQ_LAUNCH_AS(NQ_, 64, true, false);           \
-    else if (vec) KVQ_LAUNCH_AS(NQ_, 32, true, false);                   \
-    else if (from_codes) KVQ_LAUNCH_AS(NQ_, 32, false, true);            \
-    else KVQ_LAUNCH_AS(NQ_, 32, false, false);                           \
-  } while (0)
-  if (NQ == 4) KVQ_PICK_AS(4);
-  else if (NQ == 2) KVQ_PICK_AS(2);
-  else KVQ_PICK_AS(1);
-#undef KVQ_PICK_AS
-#undef KVQ_LAUNCH_AS
-  KVQ_HIP(hipGetLastError());
-  hipLaunchKernelGGL(fold_partials, dim3(1), dim3(kBlock), 0, stream, ws.sums, (const float*)nullptr,
-                     (int)blocks, (double)Q * (double)N, mean_abs_out, (float*)nullptr);
+kvq_status launch_fold_partials(const double* sums, const float* maxes, int n, double divisor, double* sum_out,
+                                float* max_out, hipStream_t stream) {
+  hipLaunchKernelGGL(fold_partials, dim3(1), dim3(kBlock), 0, stream, sums, maxes, n, divisor, sum_out, max_out);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }

@@ -191,6 +191,9 @@ kvq_status launch_roundtrip_error_dense(const float* x, const float* x_hat, int6
 kvq_status launch_roundtrip_error_codes(const float* x, const int8_t* codes, const float* scales,
                                         int64_t batch, int64_t N, int64_t D, double* sumsq_out,
                                         float* maxabs_out, hipStream_t stream);
+// folds n per-workgroup partials in index order: *sum_out = sum / divisor, *max_out = max (maxes, max_out may be null)
+kvq_status launch_fold_partials(const double* sums, const float* maxes, int n, double divisor, double* sum_out,
+                                float* max_out, hipStream_t stream);
 kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float* k, const float* k_hat,
                                    const int8_t* codes, const float* scales, int64_t N, int64_t D,
                                    double* mean_abs_out, hipStream_t stream);
