@@ -19,7 +19,8 @@ kvq_status hip_failed(hipError_t e) {
 }
 
 Options& options() {
-  static Options o;
+  // per host thread: a thread sweeping launch options changes its own launches only, and no lock is needed
+  static thread_local Options o;
   return o;
 }
 
@@ -287,36 +288,6 @@ kvq_status kvq_prepare_stream(kvq_stream_t stream) {
 
 kvq_status kvq_release_stream(kvq_stream_t stream) { return release_workspace(stream); }
 
-kvq_status kvq_plan(int call, int64_t batch, int64_t N, int64_t D, int vector_access, int compute_units,
-                    int64_t* plan_out) {
-  if (!plan_out) return KVQ_ERR_NULL;
-  if (kvq_status s = check_shape(batch, N, D)) return s;
-  if (compute_units < 1 || compute_units > 65536) return KVQ_ERR_ARG;
-  int J = 1, U = 1;
-  Tiling t;
-  if (call == KVQ_PLAN_ABSMAX) {
-    if (kvq_status s = absmax_plan(compute_units, batch, N, D, vector_access && D % 4 == 0, &J, &U, &t)) return s;
-    t.V /= J;
-  } else if (call == KVQ_PLAN_QUANTIZE || call == KVQ_PLAN_DEQUANTIZE) {
-    const int V = vector_access ? pick_width(D, nullptr, nullptr, options().codec_width) : 1;
-    const bool q = call == KVQ_PLAN_QUANTIZE;
-    if (kvq_status s = stream_tiling_for(compute_units, batch, N, D, V, V > 1, q ? kQuantUnroll : kDequantUnroll,
-                                         q ? kQuantBlock : kDequantBlock, &U, &t))
-      return s;
-  } else {
-    return KVQ_ERR_ARG;
-  }
-  plan_out[0] = t.V;
-  plan_out[1] = J;
-  plan_out[2] = t.block;
-  plan_out[3] = (int64_t)1 << t.tx_log2;
-  plan_out[4] = t.ctiles;
-  plan_out[5] = t.rchunks;
-  plan_out[6] = t.rows_per_chunk;
-  plan_out[7] = U;
-  return KVQ_OK;
-}
-
 kvq_status kvq_append_t(int dtype, const void* x_new, float* scales, float* scales_prev, int8_t* codes,
                         int64_t batch, int64_t n_old, int64_t m, int64_t capacity, int64_t D, kvq_stream_t stream) {
   if (dtype == KVQ_DTYPE_F32)
@@ -351,15 +322,6 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
   if (fused_slab_applicable(x, scales, codes, N, D)) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
   if (kvq_status s = launch_absmax_scales(x, scales, batch, N, D, stream)) return s;
   return launch_quantize(x, scales, codes, batch, N, D, stream);
-}
-
-kvq_status kvq_quantize_variant(int variant, const float* x, const float* scales, int8_t* codes, int64_t batch,
-                                int64_t N, int64_t D, kvq_stream_t stream) {
-  if (!x || !scales || !codes) return KVQ_ERR_NULL;
-  if (kvq_status s = check_shape(batch, N, D)) return s;
-  if (variant == KVQ_VARIANT_PRODUCTION) return launch_quantize(x, scales, codes, batch, N, D, stream);
-  if (variant < KVQ_VARIANT_PRODUCTION || variant > KVQ_VARIANT_VECTORIZED) return KVQ_ERR_ARG;
-  return launch_quantize_variant(variant, x, scales, codes, batch, N, D, stream);
 }
 
 kvq_status kvq_roundtrip_error(const float* x, const float* x_hat, const int8_t* codes, const float* scales,
@@ -422,75 +384,5 @@ const char* kvq_status_string(kvq_status status) {
 }
 
 int kvq_last_hip_error(void) { return g_last_hip_error; }
-
-kvq_status kvq_set_option(int key, int value) {
-  Options& o = options();
-  switch (key) {
-    case KVQ_OPT_CODEC_WIDTH:
-      if (value != 4 && value != 8 && value != 16) return KVQ_ERR_ARG;
-      o.codec_width = value;
-      return KVQ_OK;
-    case KVQ_OPT_CODEC_UNROLL:
-      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return KVQ_ERR_ARG;
-      o.codec_unroll = value;
-      return KVQ_OK;
-    case KVQ_OPT_BLOCKS_PER_CU:
-      if (value < 0 || value > 64) return KVQ_ERR_ARG;
-      o.blocks_per_cu = value;
-      return KVQ_OK;
-    case KVQ_OPT_NONTEMPORAL:
-      if (value != 0 && value != 1) return KVQ_ERR_ARG;
-      o.nontemporal = value;
-      return KVQ_OK;
-    case KVQ_OPT_BLOCK_THREADS:
-      if (value != 0 && value != 64 && value != 128 && value != 256 && value != 512) return KVQ_ERR_ARG;
-      o.block_threads = value;
-      return KVQ_OK;
-    case KVQ_OPT_PASSES_PER_BLOCK:
-      if (value < 0 || value > 65536) return KVQ_ERR_ARG;
-      o.passes_per_block = value;
-      return KVQ_OK;
-    case KVQ_OPT_ABSMAX_UNROLL:
-      if (value != 4 && value != 8 && value != 16) return KVQ_ERR_ARG;
-      o.absmax_unroll = value;
-      return KVQ_OK;
-    case KVQ_OPT_ABSMAX_PASSES:
-      if (value < 0 || value > 65536) return KVQ_ERR_ARG;
-      o.absmax_passes = value;
-      return KVQ_OK;
-    case KVQ_OPT_ABSMAX_BLOCKS_PER_CU:
-      if (value < 1 || value > 64) return KVQ_ERR_ARG;
-      o.absmax_blocks_per_cu = value;
-      return KVQ_OK;
-    case KVQ_OPT_APPEND_BLOCKS_PER_CU:
-      if (value < 1 || value > 1024) return KVQ_ERR_ARG;
-      o.append_blocks_per_cu = value;
-      return KVQ_OK;
-    case KVQ_OPT_ABSMAX_SPAN:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return KVQ_ERR_ARG;
-      o.absmax_span = value;
-      return KVQ_OK;
-    default:
-      return KVQ_ERR_ARG;
-  }
-}
-
-int kvq_get_option(int key) {
-  const Options& o = options();
-  switch (key) {
-    case KVQ_OPT_CODEC_WIDTH: return o.codec_width;
-    case KVQ_OPT_CODEC_UNROLL: return o.codec_unroll;
-    case KVQ_OPT_BLOCKS_PER_CU: return o.blocks_per_cu;
-    case KVQ_OPT_NONTEMPORAL: return o.nontemporal;
-    case KVQ_OPT_BLOCK_THREADS: return o.block_threads;
-    case KVQ_OPT_PASSES_PER_BLOCK: return o.passes_per_block;
-    case KVQ_OPT_ABSMAX_UNROLL: return o.absmax_unroll;
-    case KVQ_OPT_ABSMAX_PASSES: return o.absmax_passes;
-    case KVQ_OPT_ABSMAX_SPAN: return o.absmax_span;
-    case KVQ_OPT_ABSMAX_BLOCKS_PER_CU: return o.absmax_blocks_per_cu;
-    case KVQ_OPT_APPEND_BLOCKS_PER_CU: return o.append_blocks_per_cu;
-    default: return INT_MIN;
-  }
-}
 
 }  // extern "C"

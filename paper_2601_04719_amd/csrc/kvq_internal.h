@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "kvq.h"
+#include "kvq_bench.h"
 
 namespace kvq {
 

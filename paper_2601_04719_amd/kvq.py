@@ -1,4 +1,4 @@
-"""ctypes binding of libkvq.so: same names as include/kvq.h, argument marshalling only.
+"""ctypes binding of libkvq.so: same names as include/kvq.h and include/kvq_bench.h, argument marshalling only.
 
 Arguments may be torch tensors (anything with .data_ptr()), or raw integer
 device addresses.  `stream` is a raw hipStream_t value (for torch:
@@ -21,14 +21,19 @@ OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES, O
 OPT_ABSMAX_BLOCKS_PER_CU = 11
 OPT_APPEND_BLOCKS_PER_CU = 12
 
+# the method and its workspace calls: include/kvq.h
 EXPORTS = (
     "kvq_absmax_scales", "kvq_absmax_scales_static", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
-    "kvq_quantize_variant",
     "kvq_absmax_scales_t", "kvq_quantize_t", "kvq_dequantize_t",
-    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4", "kvq_append", "kvq_append_t", "kvq_append_int4", "kvq_plan", "kvq_prepare_stream", "kvq_release_stream",
+    "kvq_absmax_scales_int4", "kvq_quantize_int4", "kvq_dequantize_int4",
     "kvq_absmax_scales_fp8", "kvq_quantize_fp8", "kvq_dequantize_fp8",
-    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4", "kvq_probe_stream", "kvq_status_string",
-    "kvq_last_hip_error", "kvq_set_option", "kvq_get_option",
+    "kvq_append", "kvq_append_t", "kvq_append_int4",
+    "kvq_roundtrip_error", "kvq_attn_score_error", "kvq_scores_from_codes", "kvq_scores_from_codes_int4",
+    "kvq_prepare_stream", "kvq_release_stream", "kvq_status_string", "kvq_last_hip_error",
+)
+# measurement and ablation: include/kvq_bench.h
+BENCH_EXPORTS = (
+    "kvq_quantize_variant", "kvq_probe_stream", "kvq_probe_clock", "kvq_plan", "kvq_set_option", "kvq_get_option",
 )
 
 _lib = None
@@ -93,6 +98,8 @@ def lib():
         L.kvq_scores_from_codes_int4.restype = i32
         L.kvq_probe_stream.argtypes = [i32, p, p, p, p, p, i64, i64, i64, p]
         L.kvq_probe_stream.restype = i32
+        L.kvq_probe_clock.argtypes = [p, i32, p]
+        L.kvq_probe_clock.restype = i32
         L.kvq_roundtrip_error.argtypes = [p, p, p, p, i64, i64, i64, p, p, p]
         L.kvq_attn_score_error.argtypes = [p, i64, p, p, p, p, i64, i64, p, p]
         for name in ("kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_quantize_fused",
@@ -273,6 +280,10 @@ def kvq_scores_from_codes_int4(queries, Q, packed, scales, batch, N, D, scores_o
 def kvq_probe_stream(mode, src_f32, dst_f32, src_i8, dst_i8, scales, batch, N, D, stream=None):
     _check(lib().kvq_probe_stream(mode, _addr(src_f32), _addr(dst_f32), _addr(src_i8), _addr(dst_i8), _addr(scales),
                                   batch, N, D, _stream(stream)), "kvq_probe_stream")
+
+
+def kvq_probe_clock(ticks_out, microseconds, stream=None):
+    _check(lib().kvq_probe_clock(_addr(ticks_out), microseconds, _stream(stream)), "kvq_probe_clock")
 
 
 def kvq_status_string(status):

@@ -1,14 +1,14 @@
 """Times every entry point of libkvq.so on each of the five configurations and prints a markdown table.
 
-Usage:  python -m paper_2601_04719_amd.report [--configs 1,2,3,4,5] [--iters 20]
-        python -m paper_2601_04719_amd.report --sixteen          (fp16 / bf16 matrices)
-        python -m paper_2601_04719_amd.report --int4             (4-bit codes, two per byte)
-        python -m paper_2601_04719_amd.report --append           (streaming append onto an int8 cache)
-        python -m paper_2601_04719_amd.report --graph            (small configurations: eager launches vs one HIP graph)
-        python -m paper_2601_04719_amd.report --fp8              (FP8 E4M3 codes)
-        python -m paper_2601_04719_amd.report --scores-int4      (attention scores straight from a 4-bit cache)
-        python -m paper_2601_04719_amd.report --scores           (attention scores straight from int8 codes)
-        python -m paper_2601_04719_amd.report --paper-sweep      (the paper's eight shapes, uniform fills in
+Usage:  python report.py [--configs 1,2,3,4,5] [--iters 20]
+        python report.py --sixteen          (fp16 / bf16 matrices)
+        python report.py --int4             (4-bit codes, two per byte)
+        python report.py --append           (streaming append onto an int8 cache)
+        python report.py --graph            (small configurations: eager launches vs one HIP graph)
+        python report.py --fp8              (FP8 E4M3 codes)
+        python report.py --scores-int4      (attention scores straight from a 4-bit cache)
+        python report.py --scores           (attention scores straight from int8 codes)
+        python report.py --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
                                                                   the production kernel, and its two error
                                                                   figures computed on the GPU)
@@ -35,7 +35,7 @@ def main():
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     args = ap.parse_args()
     import torch
-    from . import kvq, workloads as W
+    from paper_2601_04719_amd import kvq, workloads as W
 
     stream = torch.cuda.current_stream()
 

@@ -10,27 +10,34 @@ import pytest
 from paper_2601_04719_amd import kvq
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "kvq.h")
+HEADER = os.path.join(ROOT, "include", "kvq.h")              # the method
+BENCH_HEADER = os.path.join(ROOT, "include", "kvq_bench.h")  # measurement and ablation
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(kvq_[a-z_0-9]+)\s*\(", text)))
 
 
-def test_header_and_binding_list_the_same_entry_points():
-    names = declared_functions()
+def test_headers_and_binding_list_the_same_entry_points():
+    names = declared_functions(HEADER)
     assert {"kvq_absmax_scales", "kvq_quantize", "kvq_dequantize", "kvq_roundtrip_error",
             "kvq_attn_score_error"} <= set(names)
     assert sorted(kvq.EXPORTS) == names
-    for n in names:
+    bench = declared_functions(BENCH_HEADER)
+    assert sorted(kvq.BENCH_EXPORTS) == bench
+    assert not set(names) & set(bench)
+    # the method's header carries no measurement machinery
+    assert not [n for n in names if re.search(r"probe|option|plan|variant", n)]
+    for n in names + bench:
         assert callable(getattr(kvq, n)), n
 
 
-def test_header_and_binding_agree_on_every_constant():
-    text = open(HEADER).read()
-    defines = dict(re.findall(r"^#define KVQ_([A-Z0-9_]+)\s+\(?(-?\d+)\)?", text, flags=re.M))
+def test_headers_and_binding_agree_on_every_constant():
+    defines = {}
+    for header in (HEADER, BENCH_HEADER):
+        defines.update(re.findall(r"^#define KVQ_([A-Z0-9_]+)\s+\(?(-?\d+)\)?", open(header).read(), flags=re.M))
     assert len(defines) >= 25
     for name, value in defines.items():
         assert hasattr(kvq, name), "kvq.py lacks %s" % name
@@ -39,7 +46,7 @@ def test_header_and_binding_agree_on_every_constant():
 
 def test_library_exports_every_declared_symbol():
     L = kvq.lib()
-    for n in declared_functions():
+    for n in declared_functions(HEADER) + declared_functions(BENCH_HEADER):
         assert getattr(L, n) is not None
 
 
@@ -74,6 +81,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.kvq_attn_score_error(fake, 0, fake, fake, None, None, 4, 4, fake, None) == kvq.ERR_SHAPE
     assert L.kvq_attn_score_error(fake, 2, fake, None, None, None, 4, 4, fake, None) == kvq.ERR_NULL
     assert L.kvq_attn_score_error(None, 2, fake, fake, None, None, 4, 4, fake, None) == kvq.ERR_NULL
+    assert L.kvq_probe_clock(None, 10, None) == kvq.ERR_NULL
+    assert L.kvq_probe_clock(fake, 0, None) == kvq.ERR_ARG
+    assert L.kvq_probe_clock(fake + 4, 10, None) == kvq.ERR_ARG
     # the entry point that allocates nothing: argument errors as elsewhere, and its size limit
     assert L.kvq_absmax_scales_static(None, fake, 1, 4, 4, None) == kvq.ERR_NULL
     assert L.kvq_absmax_scales_static(fake, fake, 1, 0, 4, None) == kvq.ERR_SHAPE
@@ -100,6 +110,29 @@ def test_options_round_trip_and_reject_bad_values():
         kvq.kvq_set_option(key, old)
     with pytest.raises(kvq.KvqError):
         kvq.kvq_set_option(99, 1)
+
+
+def test_options_belong_to_the_calling_thread():
+    """A thread that sweeps launch options must not change another thread's launches."""
+    import threading
+    key = kvq.OPT_BLOCKS_PER_CU
+    mine = kvq.kvq_get_option(key)
+    seen = {}
+
+    def other():
+        seen["before"] = kvq.kvq_get_option(key)      # a new thread starts from the defaults
+        kvq.kvq_set_option(key, 37)
+        seen["after"] = kvq.kvq_get_option(key)
+
+    kvq.kvq_set_option(key, 21)
+    t = threading.Thread(target=other)
+    t.start()
+    t.join()
+    try:
+        assert seen == {"before": 0, "after": 37}
+        assert kvq.kvq_get_option(key) == 21            # untouched by the other thread
+    finally:
+        kvq.kvq_set_option(key, mine)
 
 
 def test_oracle_and_product_share_no_code():
