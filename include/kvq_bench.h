@@ -81,6 +81,12 @@ kvq_status kvq_probe_clock(uint64_t *ticks_out, int microseconds, kvq_stream_t s
  *                           when ABSMAX_PASSES is 0: 1..64
  *   KVQ_OPT_APPEND_BLOCKS_PER_CU  target workgroups per compute unit of the requantization
  *                           pass of kvq_append (its row chunking): 1..1024
+ *   KVQ_OPT_FUSED_MIN_LANES narrowest column tile kvq_quantize_fused may cut a slab into, in lanes of
+ *                           4 channels along a row (4, 8, 16, 32, ...; default 8 = 128-byte row
+ *                           segments of x, 32-byte segments of codes); slabs that would need narrower
+ *                           tiles take the two-pass path
+ *   KVQ_OPT_FUSED_MAX_ROWS  rows of its tile a lane of that kernel holds in registers: 4, 8 or 16;
+ *                           0 = 8 where the tiles stay at least FUSED_MIN_LANES wide, else 16
  */
 #define KVQ_OPT_CODEC_WIDTH 1
 #define KVQ_OPT_CODEC_UNROLL 2
@@ -93,6 +99,8 @@ kvq_status kvq_probe_clock(uint64_t *ticks_out, int microseconds, kvq_stream_t s
 #define KVQ_OPT_ABSMAX_SPAN 10
 #define KVQ_OPT_ABSMAX_BLOCKS_PER_CU 11
 #define KVQ_OPT_APPEND_BLOCKS_PER_CU 12
+#define KVQ_OPT_FUSED_MIN_LANES 13
+#define KVQ_OPT_FUSED_MAX_ROWS 14
 /*
  * The launch plan of a streaming call for a shape, computed on the host without touching a
  * device: how scale reduction, quantize or dequantize (fp32 matrices, current options) would

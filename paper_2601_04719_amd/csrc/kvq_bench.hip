@@ -185,6 +185,14 @@ kvq_status kvq_set_option(int key, int value) {
       if (value != 1 && value != 2 && value != 4 && value != 8) return KVQ_ERR_ARG;
       o.absmax_span = value;
       return KVQ_OK;
+    case KVQ_OPT_FUSED_MIN_LANES:
+      if (value < 4 || value > 1024 || (value & (value - 1))) return KVQ_ERR_ARG;
+      o.fused_min_lanes = value;
+      return KVQ_OK;
+    case KVQ_OPT_FUSED_MAX_ROWS:
+      if (value != 0 && value != 4 && value != 8 && value != 16) return KVQ_ERR_ARG;
+      o.fused_max_rows = value;
+      return KVQ_OK;
     default:
       return KVQ_ERR_ARG;
   }
@@ -204,6 +212,8 @@ int kvq_get_option(int key) {
     case KVQ_OPT_ABSMAX_SPAN: return o.absmax_span;
     case KVQ_OPT_ABSMAX_BLOCKS_PER_CU: return o.absmax_blocks_per_cu;
     case KVQ_OPT_APPEND_BLOCKS_PER_CU: return o.append_blocks_per_cu;
+    case KVQ_OPT_FUSED_MIN_LANES: return o.fused_min_lanes;
+    case KVQ_OPT_FUSED_MAX_ROWS: return o.fused_max_rows;
     default: return INT_MIN;
   }
 }

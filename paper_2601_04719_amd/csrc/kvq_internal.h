@@ -72,6 +72,8 @@ struct Options {
   int absmax_span = 8;    // column groups per lane (1, 2, 4, 8), capped by the row width
   int absmax_passes = 0;  // 0 = long row chunks sized from blocks_per_cu
   int append_blocks_per_cu = 32;  // row chunking of the requantization pass of kvq_append
+  int fused_min_lanes = 8;        // narrowest column tile of the single-pass fused kernel, in 16-byte lanes along a row
+  int fused_max_rows = 0;         // rows a lane of that kernel holds: 4, 8, 16, or 0 = 8 where the tiles stay wide enough, else 16
 };
 Options& options();
 

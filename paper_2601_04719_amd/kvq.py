@@ -20,6 +20,8 @@ OPT_CODEC_WIDTH, OPT_CODEC_UNROLL, OPT_BLOCKS_PER_CU, OPT_NONTEMPORAL = 1, 2, 3,
 OPT_BLOCK_THREADS, OPT_PASSES_PER_BLOCK, OPT_ABSMAX_UNROLL, OPT_ABSMAX_PASSES, OPT_ABSMAX_SPAN = 6, 7, 8, 9, 10
 OPT_ABSMAX_BLOCKS_PER_CU = 11
 OPT_APPEND_BLOCKS_PER_CU = 12
+OPT_FUSED_MIN_LANES = 13
+OPT_FUSED_MAX_ROWS = 14
 
 # the method and its workspace calls: include/kvq.h
 EXPORTS = (

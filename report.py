@@ -8,6 +8,9 @@ Usage:  python report.py [--configs 1,2,3,4,5] [--iters 20]
         python report.py --fp8              (FP8 E4M3 codes)
         python report.py --scores-int4      (attention scores straight from a 4-bit cache)
         python report.py --scores           (attention scores straight from int8 codes)
+        python report.py --fused            (kvq_quantize_fused against the two calls, by column-tile width;
+                                             with --calibration-copy a plain copy of known size is appended
+                                             for scaling rocprofv3 --pmc counters)
         python report.py --paper-sweep      (the paper's eight shapes, uniform fills in
                                                                   [-1, 1], its four kernel designs next to
                                                                   the production kernel, and its two error
@@ -33,6 +36,9 @@ def main():
     ap.add_argument("--fp8", action="store_true", help="FP8 (E4M3) codes: absmax, quantize, dequantize, errors")
     ap.add_argument("--scores-int4", action="store_true", help="kvq_scores_from_codes_int4 on decode-like shapes")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
+    ap.add_argument("--fused", action="store_true", help="kvq_quantize_fused by column-tile width vs two passes")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="with --fused: end with one plain 512 MiB device copy (known traffic for --pmc scaling)")
     args = ap.parse_args()
     import torch
     from paper_2601_04719_amd import kvq, workloads as W
@@ -55,6 +61,63 @@ def main():
         torch.cuda.synchronize()
         t = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.iters)]
         return float(np.mean(t)), float(np.min(t))
+
+    if args.fused and args.iters == 0:
+        # for rocprofv3 --pmc: exactly one launch of each form, in this order, then a plain copy of known size
+        kvq.kvq_prepare_stream()
+        saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES)
+        for (B, N, D, lanes) in [(256, 4096, 128, 4), (256, 2048, 256, 8), (512, 1024, 256, 8), (4096, 512, 128, 8)]:
+            E = B * N * D
+            x = torch.randn(E, device="cuda")
+            scales = torch.empty(B * D, device="cuda")
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            torch.cuda.synchronize()
+            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
+            kvq.kvq_quantize_fused(x, scales, codes, B, N, D)
+            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved)
+            kvq.kvq_absmax_scales(x, scales, B, N, D)
+            kvq.kvq_quantize(x, scales, codes, B, N, D)
+            torch.cuda.synchronize()
+            print("launched: fused with tiles of >= %d lanes, then the two calls, on [%d x %d x %d]" % (lanes, B, N, D))
+            del x, codes
+            torch.cuda.empty_cache()
+        a = torch.empty(1 << 27, device="cuda")
+        b = torch.empty(1 << 27, device="cuda")
+        b.copy_(a)
+        torch.cuda.synchronize()
+        return
+
+    if args.fused:
+        print("| batch x N x D | two calls ms | fused (default) ms | 16 rows/lane, tiles >= 8 lanes | 16 rows, >= 4 lanes | 8 rows, >= 8 lanes | 8 rows, >= 4 lanes | 4 rows, >= 4 lanes |")
+        print("|---|---|---|---|---|---|---|---|")
+        saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS)
+        for (B, N, D) in [(256, 4096, 128), (256, 2048, 256), (512, 1024, 256), (64, 1024, 2048), (4096, 512, 128),
+                          (8192, 256, 128), (1, 1024, 64)]:
+            E = B * N * D
+            x = torch.randn(E, device="cuda")
+            scales = torch.empty(B * D, device="cuda")
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            two, _ = timeit(lambda: (kvq.kvq_absmax_scales(x, scales, B, N, D), kvq.kvq_quantize(x, scales, codes, B, N, D)))
+            cells = []
+            for lanes, rows in (saved, (8, 16), (4, 16), (8, 8), (4, 8), (4, 4)):
+                kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
+                kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, rows)
+                t, _ = timeit(lambda: kvq.kvq_quantize_fused(x, scales, codes, B, N, D))
+                cells.append("%.4f (%.3f)" % (t, 5.0 * E / t / 1e6 / 8000.0))
+            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved[0])
+            kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, saved[1])
+            print("| %d x %d x %d | %.4f | %s |" % (B, N, D, two, " | ".join(cells)))
+            sys.stdout.flush()
+            del x, codes
+            torch.cuda.empty_cache()
+        print()
+        print("(in brackets: fraction of 8 TB/s at 5 B per element; a setting whose tiles do not fit falls back to the two calls)")
+        if args.calibration_copy:
+            a = torch.empty(1 << 27, device="cuda")
+            b = torch.empty(1 << 27, device="cuda")
+            b.copy_(a)
+            torch.cuda.synchronize()
+        return
 
     if args.sixteen:
         print("| format | batch x N x D | absmax ms (GB/s, of 8 TB/s) | quantize ms (GB/s, of 8 TB/s) | dequantize ms (GB/s, of 8 TB/s) |")
@@ -330,7 +393,9 @@ def main():
             extra = ""
             if name.startswith("attn"):
                 tf = 2.0 * c.n_queries * N * D / (m * 1e-3) / 1e12
-                extra = " (%.1f TFLOP/s fp64, %.2f of 78.6)" % (tf, tf / 78.6)
+                bound_ms = max(2.0 * c.n_queries * N * D / 157.3e12, nbytes / 8e12) * 1e3
+                extra = " (%.1f TFLOP/s on the fp32 matrix cores; %.2f of max(157.3 TFLOP/s, 8 TB/s) = %.4f ms)" % (
+                    tf, bound_ms / m, bound_ms)
             print("| %d | %s | %s | %.4f | %.4f | %.4f | %.0f%s | %.3f |" % (cfg, shape, name, m, lo, nbytes / 1e9, gbps, extra, gbps / 8000.0))
             sys.stdout.flush()
         del x, codes, xh

@@ -536,21 +536,34 @@ def test_typed_calls_forward_fp32():
 
 
 FUSED_SHAPES = [(7, 512, 128), (3, 1000, 64), (2, 16, 4096), (5, 17, 20), (1, 16384, 4), (1, 16385, 4),
-                (4, 2048, 32), (9, 1, 8), (2, 513, 128), (1, 65, 1024), (300, 64, 64)]
+                (4, 2048, 32), (9, 1, 8), (2, 513, 128), (1, 65, 1024), (300, 64, 64),
+                # slabs cut into column tiles of a few 16-byte groups, all rows in one workgroup: slab counts that
+                # do and do not fill the eight XCD queues, ragged row counts, tiles that overhang the last channel
+                (3, 4096, 128), (9, 3000, 64), (1, 2048, 256), (5, 1500, 1000), (2, 4, 8192), (10, 4096, 16),
+                (17, 4095, 20), (8, 1025, 136), (1, 4097, 128), (2, 700, 4100)]
 
 
 @pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_single_pass_fused_slabs(shape):
-    """Slabs at, below and just above what one workgroup's registers hold."""
+    """Slabs at, below and just above what one workgroup's registers hold, whole or cut by column tile."""
     rng = np.random.default_rng(sum(shape))
     x = make_matrix(rng, *shape)
     s_ref = oracle.compute_scales(x)
     q_ref = oracle.quantize(x, s_ref)
-    g = Gpu(x)
-    s_f, q_f = g.quantize_fused()
-    assert_bits_equal(s_f, s_ref, "fused scales")
-    assert_bits_equal(q_f, q_ref, "fused codes")
-    assert g.guards_intact()
+    saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS)
+    try:
+        # the defaults; the narrowest column tiles with every register depth; wide tiles only
+        for min_lanes, max_rows in (saved, (4, 16), (4, 8), (4, 4), (64, 0)):
+            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, min_lanes)
+            kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, max_rows)
+            g = Gpu(x)
+            s_f, q_f = g.quantize_fused()
+            assert_bits_equal(s_f, s_ref, "fused scales (min lanes %d, rows %d)" % (min_lanes, max_rows))
+            assert_bits_equal(q_f, q_ref, "fused codes (min lanes %d, rows %d)" % (min_lanes, max_rows))
+            assert g.guards_intact()
+    finally:
+        kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved[0])
+        kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, saved[1])
 
 
 # ------------------------------------------------------------------ every launch shape, same bits
