@@ -28,7 +28,13 @@ __device__ __forceinline__ uint32_t code_byte(float x, float div) {
 }
 
 // int8 code of x by the divide-free quotient (see quotient_by): what the vector kernel runs, because with
-// the divide sequence it was bound by the vector ALUs, not by HBM
+// the divide sequence it was bound by the vector ALUs, not by HBM.
+// Tried on top of it and not kept: an fp32-only fast form (y = x * fl(1 / div), exact unless y lies within
+// 2^-15 of a half-integer, with the exact form as the fall-back for the wavefront).  It is correct, but
+// 16-bit inputs put near-ties everywhere: a value that is exactly half the column's absmax gives a quotient
+// within an ulp of 63.5, and such values recur because a binade holds only 128 (bf16) or 1024 (fp16)
+// different numbers -- 1.3e-3 of all bf16 elements of a Gaussian matrix, so every second wavefront piece
+// took the fall-back and the kernel ran at 0.64-0.78 ms instead of 0.50 ms on [131072 x 8192].
 __device__ __forceinline__ uint32_t code_byte_r(float x, double r) {
   float y = quotient_by(x, r);
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
