@@ -1,87 +1,64 @@
-// Ablation points: gfx950 renditions of the four kernel designs the paper compares
-// ("GPU Kernel Variants": naive, tiled, coarsened, vectorized), so that its qualitative findings
-// (staging scales in shared memory buys nothing; wider memory operations are what helps) can be
-// re-measured on CDNA4 next to the production kernel.  They are written from the paper's
-// descriptions of the four work mappings; the arithmetic is the production one (IEEE divide, clamp,
-// round-half-to-even, zero-scale guard), so all five produce identical codes.  Launch shapes the
-// paper does not state: workgroups are 64 channels x 4 tokens (one wavefront per token row); the
-// coarsened design walks tokens with as many grid rows as give about 16 workgroups per compute unit.
+// Ablation points: the four work mappings the paper compares ("GPU Kernel Variants": naive, tiled,
+// coarsened, vectorized) as gfx950 kernels, so that its qualitative findings (staging scales in shared
+// memory buys nothing; wider memory operations are what helps) can be re-measured on CDNA4 next to the
+// production kernel.  Only the mappings are the paper's -- one lane per element / the workgroup's scales
+// staged in LDS / one lane per channel walking down the tokens / four adjacent channels per lane.  The
+// kernels are this library's: one kernel over the library's work-item decomposition (a 1-D grid decoded
+// into slab, row chunk and column tile, 64-bit indices, any shape), with the production arithmetic (IEEE
+// divide, clamp, round-half-to-even, zero-scale guard), so all five designs produce identical codes.
+// Launch shapes the paper does not state: workgroups are 64 lanes along a row x 4 rows (one wavefront per
+// row); the coarsened design gets row chunks that give about 16 workgroups per compute unit.
+#include <limits.h>
+
 #include "kvq_internal.h"
 
 namespace kvq {
 
-constexpr int kAbX = 64, kAbY = 4;
+constexpr int kAbTxLog2 = 6, kAbBlock = 256;  // 64 x 4 lanes
+enum AbMode { kAbNaive, kAbTiled, kAbCoarsened, kAbVectorized };
 
-__device__ __forceinline__ int8_t ab_code(float x, float s) {
-  const float d = divisor_of(s);
-  float y = x / d;
+__device__ __forceinline__ uint32_t ab_code(float x, float s) {
+  float y = x / divisor_of(s);
   y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
-  return (int8_t)(__float_as_uint(y + kRoundMagic) & 0xffu);
+  return __float_as_uint(y + kRoundMagic) & 0xffu;
 }
 
-// "naive": one lane per element; every lane fetches its own scale.
-__global__ __launch_bounds__(kAbX* kAbY) void ab_naive(const float* __restrict__ x, const float* __restrict__ scales,
-                                                      int8_t* __restrict__ codes, int64_t N, int64_t D,
-                                                      uint32_t row_blocks) {
-  const int64_t slab = blockIdx.y / row_blocks;
-  const int64_t t = (int64_t)(blockIdx.y % row_blocks) * kAbY + threadIdx.y;
-  const int64_t d = (int64_t)blockIdx.x * kAbX + threadIdx.x;
-  if (t < N && d < D) {
-    const int64_t i = (slab * N + t) * D + d;
-    codes[i] = ab_code(x[i], scales[slab * D + d]);
+template <int MODE>
+__global__ __launch_bounds__(kAbBlock) void ablation_kernel(const float* __restrict__ x,
+                                                            const float* __restrict__ scales,
+                                                            int8_t* __restrict__ codes, int64_t N, int64_t D,
+                                                            uint32_t ctiles, uint32_t rchunks, int64_t rows_per_chunk,
+                                                            int64_t groups) {
+  constexpr int V = MODE == kAbVectorized ? 4 : 1;
+  __shared__ float staged[1 << kAbTxLog2];
+  const Item it = decode_item(blockIdx.x, ctiles, rchunks, rows_per_chunk, N, kAbTxLog2);
+  const bool active = it.group < groups;
+  const int64_t col = it.group * V;
+  const float* sp = scales + it.slab * D + col;
+  if constexpr (MODE == kAbTiled) {
+    // the lanes of the workgroup's first row fetch the tile's scales once; every row then reads them from LDS
+    if (it.ty == 0 && active) staged[threadIdx.x] = *sp;
+    __syncthreads();
   }
-}
-
-// "tiled": the workgroup's 64 scales are staged in LDS by its first token row, then shared.
-__global__ __launch_bounds__(kAbX* kAbY) void ab_tiled(const float* __restrict__ x, const float* __restrict__ scales,
-                                                      int8_t* __restrict__ codes, int64_t N, int64_t D,
-                                                      uint32_t row_blocks) {
-  __shared__ float s_tile[kAbX];
-  const int64_t slab = blockIdx.y / row_blocks;
-  const int64_t t = (int64_t)(blockIdx.y % row_blocks) * kAbY + threadIdx.y;
-  const int64_t d = (int64_t)blockIdx.x * kAbX + threadIdx.x;
-  if (threadIdx.y == 0 && d < D) s_tile[threadIdx.x] = scales[slab * D + d];
-  __syncthreads();
-  if (t < N && d < D) {
-    const int64_t i = (slab * N + t) * D + d;
-    codes[i] = ab_code(x[i], s_tile[threadIdx.x]);
-  }
-}
-
-// "coarsened": one lane per channel keeps its scale in a register and walks down the tokens,
-// gridDim.y workgroup rows apart.
-__global__ __launch_bounds__(kAbX* kAbY) void ab_coarsened(const float* __restrict__ x,
-                                                          const float* __restrict__ scales,
-                                                          int8_t* __restrict__ codes, int64_t N, int64_t D,
-                                                          uint32_t walkers) {
-  const int64_t slab = blockIdx.y / walkers;
-  const int64_t d = (int64_t)blockIdx.x * kAbX + threadIdx.x;
-  if (d >= D) return;
-  const float s = scales[slab * D + d];
-  const int64_t stride = (int64_t)walkers * kAbY;
-  for (int64_t t = (int64_t)(blockIdx.y % walkers) * kAbY + threadIdx.y; t < N; t += stride) {
-    const int64_t i = (slab * N + t) * D + d;
-    codes[i] = ab_code(x[i], s);
-  }
-}
-
-// "vectorized": four adjacent channels per lane: one 16-byte load of x and of the scales, one
-// 4-byte store of codes.  Needs D % 4 == 0 and 16-byte aligned rows.
-__global__ __launch_bounds__(kAbX* kAbY) void ab_vectorized(const float* __restrict__ x,
-                                                           const float* __restrict__ scales,
-                                                           int8_t* __restrict__ codes, int64_t N, int64_t D,
-                                                           uint32_t row_blocks) {
-  const int64_t slab = blockIdx.y / row_blocks;
-  const int64_t t = (int64_t)(blockIdx.y % row_blocks) * kAbY + threadIdx.y;
-  const int64_t d = ((int64_t)blockIdx.x * kAbX + threadIdx.x) * 4;
-  if (t < N && d < D) {
-    const int64_t i = (slab * N + t) * D + d;
-    const f32x4 v = *reinterpret_cast<const f32x4*>(x + i);
-    const f32x4 s = *reinterpret_cast<const f32x4*>(scales + slab * D + d);
-    uint32_t w = 0;
+  if (!active) return;
+  float kept = 0.0f;
+  if constexpr (MODE == kAbCoarsened) kept = *sp;  // in a register for the whole walk
+  for (int64_t row = it.row0 + it.ty; row < it.row1; row += it.TY) {
+    const int64_t i = (it.slab * N + row) * D + col;
+    if constexpr (MODE == kAbVectorized) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(x + i);
+      const f32x4 s = *reinterpret_cast<const f32x4*>(sp);  // fetched again for every element, as in the design
+      uint32_t w = 0;
 #pragma unroll
-    for (int k = 0; k < 4; k++) w |= (uint32_t)(uint8_t)ab_code(v[k], s[k]) << (8 * k);
-    *reinterpret_cast<uint32_t*>(codes + i) = w;
+      for (int k = 0; k < 4; k++) w |= ab_code(v[k], s[k]) << (8 * k);
+      *reinterpret_cast<uint32_t*>(codes + i) = w;
+    } else {
+      float s;
+      if constexpr (MODE == kAbNaive) s = *sp;
+      else if constexpr (MODE == kAbTiled) s = staged[threadIdx.x & ((1 << kAbTxLog2) - 1)];
+      else s = kept;
+      codes[i] = (int8_t)ab_code(x[i], s);
+    }
   }
 }
 
@@ -89,40 +66,34 @@ kvq_status launch_quantize_variant(int variant, const float* x, const float* sca
                                    int64_t batch, int64_t N, int64_t D, hipStream_t stream) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
-  const dim3 block(kAbX, kAbY);
-  const int64_t row_blocks = (N + kAbY - 1) / kAbY;
-  const int64_t lanes_x = variant == KVQ_VARIANT_VECTORIZED ? D / 4 : D;
-  const int64_t gx = (lanes_x + kAbX - 1) / kAbX;
-  if (gx > INT32_MAX) return KVQ_ERR_OVERFLOW;
-  if (variant == KVQ_VARIANT_COARSENED) {
-    int64_t walkers = ((int64_t)dev.cus * 16 + gx * batch - 1) / (gx * batch);
-    if (walkers < 1) walkers = 1;
-    if (walkers > row_blocks) walkers = row_blocks;
-    if (batch * walkers > 65535) return KVQ_ERR_OVERFLOW;
-    hipLaunchKernelGGL(ab_coarsened, dim3((uint32_t)gx, (uint32_t)(batch * walkers)), block, 0, stream, x, scales,
-                       codes, N, D, (uint32_t)walkers);
-    KVQ_HIP(hipGetLastError());
-    return KVQ_OK;
-  }
-  // the 2-D designs put (slab, token block) on grid.y, which holds at most 65535 rows: larger problems
-  // are issued as several launches over row ranges
   if (variant == KVQ_VARIANT_VECTORIZED && (D % 4 || !aligned(x, 16) || !aligned(scales, 16) || !aligned(codes, 4)))
     return KVQ_ERR_ARG;
-  const int64_t max_rows_per_launch = (int64_t)65535 * kAbY;
-  for (int64_t b = 0; b < batch; b++) {
-    for (int64_t r0 = 0; r0 < N; r0 += max_rows_per_launch) {
-      const int64_t n = N - r0 < max_rows_per_launch ? N - r0 : max_rows_per_launch;
-      const uint32_t rb = (uint32_t)((n + kAbY - 1) / kAbY);
-      const float* xp = x + (b * N + r0) * D;
-      int8_t* cp = codes + (b * N + r0) * D;
-      const float* sp = scales + b * D;
-      const dim3 grid((uint32_t)gx, rb);
-      if (variant == KVQ_VARIANT_NAIVE) hipLaunchKernelGGL(ab_naive, grid, block, 0, stream, xp, sp, cp, n, D, rb);
-      else if (variant == KVQ_VARIANT_TILED) hipLaunchKernelGGL(ab_tiled, grid, block, 0, stream, xp, sp, cp, n, D, rb);
-      else hipLaunchKernelGGL(ab_vectorized, grid, block, 0, stream, xp, sp, cp, n, D, rb);
-      KVQ_HIP(hipGetLastError());
-    }
+  const int V = variant == KVQ_VARIANT_VECTORIZED ? 4 : 1;
+  const int64_t TX = (int64_t)1 << kAbTxLog2, TY = kAbBlock / TX;
+  const int64_t groups = (D + V - 1) / V;
+  const int64_t ctiles = (groups + TX - 1) / TX;
+  // one row per lane, except for the coarsened design, whose lanes walk a long row chunk
+  int64_t rows = TY;
+  if (variant == KVQ_VARIANT_COARSENED) {
+    int64_t walkers = ((int64_t)dev.cus * 16 + ctiles * batch - 1) / (ctiles * batch);
+    if (walkers < 1) walkers = 1;
+    rows = (N + walkers - 1) / walkers;
+    rows = (rows + TY - 1) / TY * TY;
   }
+  const int64_t rchunks = (N + rows - 1) / rows;
+  if (ctiles > INT32_MAX || rchunks > INT32_MAX || batch > INT32_MAX / ctiles ||
+      batch * ctiles > INT32_MAX / rchunks)
+    return KVQ_ERR_OVERFLOW;
+  const dim3 grid((uint32_t)(batch * rchunks * ctiles)), block(kAbBlock);
+#define KVQ_AB(MODE_)                                                                                        \
+  hipLaunchKernelGGL((ablation_kernel<MODE_>), grid, block, 0, stream, x, scales, codes, N, D, (uint32_t)ctiles, \
+                     (uint32_t)rchunks, rows, groups)
+  if (variant == KVQ_VARIANT_NAIVE) KVQ_AB(kAbNaive);
+  else if (variant == KVQ_VARIANT_TILED) KVQ_AB(kAbTiled);
+  else if (variant == KVQ_VARIANT_COARSENED) KVQ_AB(kAbCoarsened);
+  else KVQ_AB(kAbVectorized);
+#undef KVQ_AB
+  KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }
 
