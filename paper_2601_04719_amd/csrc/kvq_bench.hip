@@ -122,7 +122,7 @@ kvq_status kvq_plan(int call, int64_t batch, int64_t N, int64_t D, int vector_ac
     const int V = vector_access ? pick_width(D, nullptr, nullptr, options().codec_width) : 1;
     const bool q = call == KVQ_PLAN_QUANTIZE;
     if (kvq_status s = stream_tiling_for(compute_units, batch, N, D, V, V > 1, q ? kQuantUnroll : kDequantUnroll,
-                                         q ? kQuantBlock : kDequantBlock, &U, &t))
+                                         q ? kQuantBlock : dequant_block_for(D), &U, &t))
       return s;
   } else {
     return KVQ_ERR_ARG;

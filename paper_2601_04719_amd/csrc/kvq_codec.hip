@@ -275,7 +275,7 @@ kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_
                              int64_t N, int64_t D, hipStream_t stream) {
   int U;
   Tiling t;
-  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, kDequantUnroll, kDequantBlock, &U, &t)) return s;
+  if (kvq_status s = codec_tiling(batch, N, D, x_hat, codes, scales, kDequantUnroll, dequant_block_for(D), &U, &t)) return s;
   const bool nt = options().nontemporal != 0;
   return dispatch_vu(t.V, U, [&](auto v, auto u) {
     return launch_d<decltype(v)::value, decltype(u)::value>(codes, scales, x_hat, N, D, t, nt, stream);
@@ -296,7 +296,7 @@ kvq_status launch_probe_codec(int mode, const float* src_f32, float* dst_f32, co
                        src_f32, scales, dst_i8, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups,
                        N * D, N * D);
   } else {
-    if (kvq_status s = codec_tiling(batch, N, D, dst_f32, src_i8, scales, 2, 256, &U, &t)) return s;
+    if (kvq_status s = codec_tiling(batch, N, D, dst_f32, src_i8, scales, 2, dequant_block_for(D), &U, &t)) return s;
     if (t.V != 4 || U != 2) return KVQ_ERR_ARG;
     hipLaunchKernelGGL((dequantize_kernel<4, 2, true, false>), dim3((uint32_t)t.items), dim3(t.block), 0, stream,
                        src_i8, scales, dst_f32, N, D, t.tx_log2, t.ctiles, t.rchunks, t.rows_per_chunk, t.groups);
