@@ -252,7 +252,14 @@ kvq_status kvq_roundtrip_error(const float *x, const float *x_hat,
  * attention dot products computed with original and reconstructed keys") and
  * Evaluation, "Attention Score Error":
  *   *mean_abs_out = (1/(Q*N)) sum_{j<Q, t<N} | q_j . k_t  -  q_j . k_hat_t |
- * raw dot products (no 1/sqrt(d), no softmax), accumulated in fp64.
+ * raw dot products (no 1/sqrt(d), no softmax).  Computed as sum_d q_j[d] e_t[d]
+ * with e = k - k_hat formed in fp32 (exact there), contracted on the matrix
+ * cores in runs of 64 channels that are rounded to fp32 and added up in fp64;
+ * absolute value and mean in fp64.  Every score is within
+ * 65 * 2^-24 * sum_d |q_j[d] e_t[d]| of the exact one (the errors are centred:
+ * the mean moves by far less).  Beyond finite inputs this needs the 64-channel
+ * sums of |q e| inside the fp32 range; values of |q| or |e| below 2^-110 may
+ * lose low bits.
  *   queries [Q,D] fp32, k [N,D] fp32: device, read only
  *   k_hat [N,D] fp32, or NULL with codes [N,D] int8 + scales [D] fp32 given
  *   (k_hat recomputed as in kvq_dequantize)

@@ -1,6 +1,10 @@
 // Attention-score error (paper: Introduction, "Attention score error"; Evaluation, "Attention
 // Score Error"): the mean over (query, token) of |q.k - q.k_hat|.
 //
+// This file: the launcher, and the form on the fp32 matrix cores, which takes any shape and alignment.
+// Shapes with D a multiple of 128 and aligned pointers take the faster form of kvq_attn_split.hip (the same
+// contraction on the bf16 matrix cores, bound by HBM instead of by the matrix rate).
+//
 // The score difference  q_j . k_t - q_j . k_hat_t = sum_d q_j[d] (k_t[d] - k_hat_t[d])  is a dense
 // [tokens x D] . [D x queries] contraction, and e = k - k_hat is exact in fp32 (k_hat is within a
 // factor of two of k wherever the code is not 0, and is 0 where it is).  So the contraction runs on
@@ -380,6 +384,11 @@ kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float*
   vec = vec && (from_codes ? (aligned(codes, 4) && aligned(scales, 16)) : aligned(k_hat, 16));
   // unchecked loads: whole chunks, vector access, and per-lane byte offsets (8 rows at most) within 32 bits
   const bool fast = vec && D % kChunk == 0 && D <= ((int64_t)1 << 26);
+  if (fast && attn_split_applicable(Q, D) && options().attn_form != 1) {
+    int nblocks = 0;
+    if (kvq_status s = launch_attn_split(queries, Q, k, k_hat, codes, scales, N, D, ws, &nblocks, stream)) return s;
+    return launch_fold_partials(ws.sums, nullptr, nblocks, (double)Q * (double)N, mean_abs_out, nullptr, stream);
+  }
   const dim3 grid((uint32_t)blocks), block(kBlock);
 #define KVQ_LAUNCH_AS(NQ_, VEC_, FC_, FAST_)                                                                 \
   hipLaunchKernelGGL((attn_score_kernel<NQ_, VEC_, FC_, FAST_>), grid, block, 0, stream, queries, Q, k, k_hat, \

@@ -79,6 +79,7 @@ struct Options {
   int append_blocks_per_cu = 32;  // row chunking of the requantization pass of kvq_append
   int fused_min_lanes = 8;        // narrowest column tile of the single-pass fused kernel, in 16-byte lanes along a row
   int fused_max_rows = 0;         // rows a lane of that kernel holds: 4, 8, 16, or 0 = 8 where the tiles stay wide enough, else 16
+  int attn_form = 0;              // score-error contraction: 0 = bf16 pieces where the shape allows, 1 = fp32 matrix cores always
 };
 Options& options();
 
@@ -205,6 +206,13 @@ kvq_status launch_fold_partials(const double* sums, const float* maxes, int n, d
 kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float* k, const float* k_hat,
                                    const int8_t* codes, const float* scales, int64_t N, int64_t D,
                                    double* mean_abs_out, hipStream_t stream);
+// The same contraction on the bf16 matrix cores (every fp32 operand as the exact sum of three bf16 pieces): D a
+// multiple of 128, every pointer 16-byte (codes: 4-byte) aligned, and the split queries (6 bytes per element of
+// whole 32- or 64-query chunks) within the workspace's 16 MiB.  Leaves *blocks_out partial sums in ws.sums.
+bool attn_split_applicable(int64_t Q, int64_t D);
+kvq_status launch_attn_split(const float* queries, int64_t Q, const float* k, const float* k_hat,
+                             const int8_t* codes, const float* scales, int64_t N, int64_t D, const Workspace& ws,
+                             int* blocks_out, hipStream_t stream);
 
 // ---- device helpers ----
 #ifdef __HIPCC__

@@ -22,6 +22,7 @@ OPT_ABSMAX_BLOCKS_PER_CU = 11
 OPT_APPEND_BLOCKS_PER_CU = 12
 OPT_FUSED_MIN_LANES = 13
 OPT_FUSED_MAX_ROWS = 14
+OPT_ATTN_FORM = 15
 
 # the method and its workspace calls: include/kvq.h
 EXPORTS = (

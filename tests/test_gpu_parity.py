@@ -44,11 +44,15 @@ def assert_bits_equal(a, b, what):
 
 def attn_error_bound(queries, k, k_hat):
     """Worst case of |gpu - exact| for kvq_attn_score_error.  The GPU forms e = k - k_hat exactly in fp32 and
-    contracts it with the queries on the fp32 matrix cores in runs of 64 channels: 64 products and 64
-    additions, each rounded once to fp32 (relative 2^-24), so a score is off by at most 65 * 2^-24 *
-    sum_d |q_d e_d|; runs are added, |.| taken and the mean formed in fp64 (negligible next to that).  The
-    mean of |score| is then off by at most the mean of that bound.  The errors are centred, so the observed
-    difference is orders of magnitude smaller: the tests hold the call to the 1e-5 bar and to this bound."""
+    contracts it with the queries in runs of 64 channels whose results are added in fp64.  On the fp32 matrix
+    cores a run is 64 products and 64 additions, each rounded once to fp32 (relative 2^-24): a score is off by
+    at most 65 * 2^-24 * sum_d |q_d e_d|.  On the bf16 matrix cores e and q are each the exact sum of three bf16
+    pieces and six of the nine piece products are kept: the dropped ones are below 2 * 2^-24 |q_d e_d| (+ 2^-32),
+    the kept ones are exact in fp32, and the run is 24 matrix instructions on one fp32 accumulator, taken as
+    at most two units in the last place each: (2 + 48) * 2^-24, inside the same 65 * 2^-24.  |.| and the mean
+    are fp64 (negligible next to that).  The mean of |score| is then off by at most the mean of that bound.
+    The errors are centred, so the observed difference is orders of magnitude smaller: the tests hold the
+    call to the 1e-5 bar and to this bound."""
     e = np.abs(np.asarray(k, dtype=np.float64) - np.asarray(k_hat, dtype=np.float64))
     return 65 * 2.0 ** -24 * float((np.abs(np.asarray(queries, dtype=np.float64)) @ e.T).mean())
 
@@ -288,6 +292,49 @@ def test_attn_score_error_with_more_token_tiles_than_partial_slots(N, D, Q):
     a_ref2 = oracle.attn_score_error(qs, x[0], xh_ref[0])
     assert a_ref2 > a_ref * (1 + 1e-3)
     assert g.attn_score_error(qs, from_codes=False) == pytest.approx(a_ref2, rel=REL, abs=0)
+
+
+# Shapes that take the bf16 matrix-core form (D a multiple of 128): a single ragged tile; 3 chunks; more tiles
+# than compute units, so that workgroups walk several tiles, with one-chunk tiles (the hand-over area alternates),
+# three query chunks, and 64-token tiles (N >= 64 tokens per compute unit) ending in a ragged one; few tiles.
+@pytest.mark.parametrize("N,D,Q", [(1, 128, 1), (33, 128, 3), (100, 384, 33), (257, 256, 65), (9000, 128, 64),
+                                   (5000, 640, 130), (40000, 128, 20), (16500, 256, 64), (33000, 128, 40),
+                                   (70, 1024, 64)], ids=lambda v: str(v))
+def test_attn_score_error_on_the_bf16_matrix_cores(N, D, Q):
+    rng = np.random.default_rng(seed_of("bf16 pieces", N, D, Q))
+    x = make_matrix(rng, 1, N, D)
+    qs = (rng.standard_normal((Q, D)) * np.exp(rng.uniform(-3, 3, (Q, 1)))).astype(np.float32)
+    g = Gpu(x)
+    s_ref = oracle.compute_scales(x)
+    q_ref = oracle.quantize(x, s_ref)
+    xh_ref = oracle.dequantize(q_ref, s_ref)
+    g.set_scales(s_ref)
+    g.codes.copy_(torch.from_numpy(q_ref.reshape(-1)))
+    g.xh.copy_(torch.from_numpy(xh_ref.reshape(-1)))
+    a_ref = oracle.attn_score_error(qs, x[0], xh_ref[0])
+    bound = attn_error_bound(qs, x[0], xh_ref[0])
+    saved = kvq.kvq_get_option(kvq.OPT_ATTN_FORM)
+    try:
+        got = {}
+        for form in (0, 1):            # 0: bf16 pieces (these shapes allow it), 1: fp32 matrix cores
+            kvq.kvq_set_option(kvq.OPT_ATTN_FORM, form)
+            for from_codes in (False, True):
+                a = g.attn_score_error(qs, from_codes)
+                assert a == pytest.approx(a_ref, rel=REL, abs=0), "form %d from_codes=%s" % (form, from_codes)
+                assert abs(a - a_ref) <= bound + 1e-13 * a_ref, "form %d beyond its rounding bound" % form
+                got[form, from_codes] = a
+            assert got[form, False] == got[form, True]      # the same e either way, the same arithmetic
+        kvq.kvq_set_option(kvq.OPT_ATTN_FORM, 0)
+        assert g.attn_score_error(qs, False) == got[0, False]   # same bits run to run
+        # the last tokens must really be in the mean: move the reconstruction of the last 3 tokens only
+        m = min(3, N)
+        g.xh[-m * D:] += 0.5
+        xh_ref[0, -m:] += np.float32(0.5)
+        a_ref2 = oracle.attn_score_error(qs, x[0], xh_ref[0])
+        assert a_ref2 > a_ref
+        assert g.attn_score_error(qs, from_codes=False) == pytest.approx(a_ref2, rel=REL, abs=0)
+    finally:
+        kvq.kvq_set_option(kvq.OPT_ATTN_FORM, saved)
 
 
 # ------------------------------------------------------------------ shapes, tails, alignment
