@@ -395,10 +395,14 @@ def main():
             gbps = nbytes / (m * 1e-3) / 1e9
             extra = ""
             if name.startswith("attn"):
-                tf = 2.0 * c.n_queries * N * D / (m * 1e-3) / 1e12
-                bound_ms = max(2.0 * c.n_queries * N * D / 157.3e12, nbytes / 8e12) * 1e3
-                extra = " (%.1f TFLOP/s on the fp32 matrix cores; %.2f of max(157.3 TFLOP/s, 8 TB/s) = %.4f ms)" % (
-                    tf, bound_ms / m, bound_ms)
+                flops = 2.0 * c.n_queries * N * D
+                if D % 128 == 0:   # the bf16 matrix-core form: six piece products per fp32 product
+                    extra = " (%.0f TFLOP/s on the bf16 matrix cores, 6 piece products per product; bound: HBM, %.4f ms)" % (
+                        6.0 * flops / (m * 1e-3) / 1e12, nbytes / 8e12 * 1e3)
+                else:
+                    bound_ms = max(flops / 157.3e12, nbytes / 8e12) * 1e3
+                    extra = " (%.1f TFLOP/s on the fp32 matrix cores; %.2f of max(157.3 TFLOP/s, 8 TB/s) = %.4f ms)" % (
+                        flops / (m * 1e-3) / 1e12, bound_ms / m, bound_ms)
             print("| %d | %s | %s | %.4f | %.4f | %.4f | %.0f%s | %.3f |" % (cfg, shape, name, m, lo, nbytes / 1e9, gbps, extra, gbps / 8000.0))
             sys.stdout.flush()
         del x, codes, xh
