@@ -157,6 +157,18 @@ def time_extras(kvq, torch, timer, h, x, x_hat, codes, scales, E, N, D):
     out = {}
     saved = scales.clone()
     u8 = codes.view(torch.uint8)
+    # the attention-score error of the step's own reconstruction (x_hat, codes and scales are as the step left
+    # them), 64 queries: on the first 16384 tokens (the shape of configuration 4) and on all of them
+    mean_abs = torch.zeros(1, dtype=torch.float64, device=x.device)
+    q64 = torch.randn(64 * D, device=x.device)
+    for rows in (min(16384, N), N):
+        nb = 8.0 * rows * D + 4.0 * 64 * D
+        out["attn_score_error_Q64[%dx%d]" % (rows, D)] = row(
+            lambda: kvq.kvq_attn_score_error(q64, 64, x, x_hat, None, None, rows, D, mean_abs, stream=h), nb,
+            note="k vs k_hat, 8 B per element; bf16 matrix cores")
+        out["attn_score_error_from_codes_Q64[%dx%d]" % (rows, D)] = row(
+            lambda: kvq.kvq_attn_score_error(q64, 64, x, None, codes, scales, rows, D, mean_abs, stream=h),
+            5.0 * rows * D + 4.0 * 64 * D + 4.0 * D, note="k vs codes, 5 B per element")
     out["absmax_scales_fp8+quantize_fp8"] = row(lambda: (kvq.kvq_absmax_scales_fp8(x, scales, 1, N, D, stream=h),
                                                          kvq.kvq_quantize_fp8(x, scales, u8, 1, N, D, stream=h))[1],
                                                 9.0 * E, note="two calls, 4 + 5 B per element")
