@@ -320,8 +320,9 @@ int kvq_last_hip_error(void);
 
 /*
  * Creates the current device's workspace for `stream` now (one hipMalloc; nothing happens if it
- * exists), so that the first reduction on that stream allocates nothing -- call it before capturing
- * a graph on the stream, or before entering a region that must not allocate.
+ * exists) and does the once-per-device set-up of the score-error kernels (their LDS limit), so that
+ * the first reduction on that stream allocates nothing and enqueues nothing but kernels -- call it
+ * before capturing a graph on the stream, or before entering a region that must not allocate.
  */
 kvq_status kvq_prepare_stream(kvq_stream_t stream);
 

@@ -283,7 +283,8 @@ kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int
 
 kvq_status kvq_prepare_stream(kvq_stream_t stream) {
   Workspace ws;
-  return get_workspace(stream, &ws);
+  if (kvq_status s = get_workspace(stream, &ws)) return s;
+  return prepare_attn_split();
 }
 
 kvq_status kvq_release_stream(kvq_stream_t stream) { return release_workspace(stream); }

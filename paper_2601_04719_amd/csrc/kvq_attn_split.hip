@@ -32,6 +32,7 @@
 // 16 fp64 totals.  Loads of the next chunk are issued one at a time between the matrix instructions
 // (a load waits at issue while the memory pipeline is full, and a wavefront issues in order); a B
 // operand's registers are reloaded right after the last instruction that reads them.
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -399,6 +400,30 @@ __global__ __launch_bounds__(2 * kBlock, 1) void attn_split_kernel(const void* _
 
 }  // namespace
 
+// The score-error kernels need more dynamic LDS than a kernel gets by default: raise the limit of every
+// instantiation, once per device (also from kvq_prepare_stream, so that nothing but launches is left for a
+// stream capture).
+kvq_status prepare_attn_split() {
+  static std::atomic<uint64_t> done{0};
+  int dev = -1;
+  KVQ_HIP(hipGetDevice(&dev));
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return KVQ_OK;
+#define KVQ_RAISE_LDS(NQ_, TT_, FC_)                                                                        \
+  static_assert(split_lds_bytes(NQ_, TT_) <= 160 * 1024, "LDS of one compute unit");                       \
+  KVQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<NQ_, TT_, FC_>),             \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)split_lds_bytes(NQ_, TT_)))
+  KVQ_RAISE_LDS(2, 2, true);
+  KVQ_RAISE_LDS(2, 2, false);
+  KVQ_RAISE_LDS(2, 1, true);
+  KVQ_RAISE_LDS(2, 1, false);
+  KVQ_RAISE_LDS(1, 1, true);
+  KVQ_RAISE_LDS(1, 1, false);
+#undef KVQ_RAISE_LDS
+  if (bit) done.fetch_or(bit, std::memory_order_release);
+  return KVQ_OK;
+}
+
 bool attn_split_applicable(int64_t Q, int64_t D) {
   if (D % kCh != 0 || D > ((int64_t)1 << 22)) return false;  // the 64 rows of a tile within a 31-bit byte count
   const int64_t NQ = Q > 32 ? 2 : 1;
@@ -413,6 +438,7 @@ kvq_status launch_attn_split(const float* queries, int64_t Q, const float* k, co
                              int* blocks_out, hipStream_t stream) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  if (kvq_status s = prepare_attn_split()) return s;
   const int NQ = Q > 32 ? 2 : 1;
   // 64-token tiles where there are two query tiles to feed, a tile is two chunks or longer (the kernel's
   // single hand-over area relies on it) and every compute unit still gets a tile
@@ -434,9 +460,6 @@ kvq_status launch_attn_split(const float* queries, int64_t Q, const float* k, co
 #define KVQ_LAUNCH_SPLIT(NQ_, TT_, FC_)                                                                          \
   do {                                                                                                           \
     constexpr size_t lds = split_lds_bytes(NQ_, TT_);                                                            \
-    static_assert(lds <= 160 * 1024, "LDS of one compute unit");                                                \
-    KVQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<NQ_, TT_, FC_>),                 \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                          \
     hipLaunchKernelGGL((attn_split_kernel<NQ_, TT_, FC_>), grid, block, lds, stream, (const void*)ws.colmax,     \
                        (uint32_t)qtiles, k, k_hat, codes, scales, N, D, (uint32_t)qchunks, (uint32_t)tiles,      \
                        ws.sums);                                                                                 \

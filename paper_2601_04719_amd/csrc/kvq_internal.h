@@ -210,6 +210,8 @@ kvq_status launch_attn_score_error(const float* queries, int64_t Q, const float*
 // multiple of 128, every pointer 16-byte (codes: 4-byte) aligned, and the split queries (6 bytes per element of
 // whole 32- or 64-query chunks) within the workspace's 16 MiB.  Leaves *blocks_out partial sums in ws.sums.
 bool attn_split_applicable(int64_t Q, int64_t D);
+// one-time set-up of those kernels on the current device (their LDS limit); called by the launcher as well
+kvq_status prepare_attn_split();
 kvq_status launch_attn_split(const float* queries, int64_t Q, const float* k, const float* k_hat,
                              const int8_t* codes, const float* scales, int64_t N, int64_t D, const Workspace& ws,
                              int* blocks_out, hipStream_t stream);

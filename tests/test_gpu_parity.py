@@ -1199,6 +1199,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     g = Gpu(xs[0])
     packed = torch.zeros(batch * N * D // 2, dtype=torch.uint8, device="cuda")
     s4 = torch.zeros(batch * D, dtype=torch.float32, device="cuda")
+    qs = torch.from_numpy(rng.standard_normal((5, D)).astype(np.float32)).cuda()
+    mean2 = torch.zeros(1, dtype=torch.float64, device="cuda")
 
     def step():
         kvq.kvq_absmax_scales(g.x, g.scales, batch, N, D)
@@ -1207,10 +1209,13 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         kvq.kvq_roundtrip_error(g.x, g.xh, None, None, batch, N, D, g.sumsq, g.maxabs)
         kvq.kvq_absmax_scales_int4(g.x, s4, batch, N, D)
         kvq.kvq_quantize_int4(g.x, s4, packed, batch, N, D)
+        # the score error of the first slab, both forms (rows of 128 channels: the bf16 matrix-core kernels)
+        kvq.kvq_attn_score_error(qs, 5, g.x, g.xh, None, None, N, D, g.mean)
+        kvq.kvq_attn_score_error(qs, 5, g.x, None, g.codes, g.scales, N, D, mean2)
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (g.scales, g.codes, g.xh, g.sumsq, g.maxabs, s4, packed)]
+        return [t.clone() for t in (g.scales, g.codes, g.xh, g.sumsq, g.maxabs, s4, packed, g.mean, mean2)]
 
     side = torch.cuda.Stream()
     kvq.kvq_prepare_stream(side.cuda_stream)    # this stream's workspace exists before the capture
@@ -1226,6 +1231,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
             t.fill_(-1.0)
         g.codes.fill_(77)
         packed.fill_(0x33)
+        g.mean.fill_(-1.0)
+        mean2.fill_(-1.0)
         torch.cuda.synchronize()
         graph.replay()
         got = snapshot()
