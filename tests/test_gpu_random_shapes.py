@@ -129,3 +129,34 @@ def test_random_shapes_sixteen_bit_inputs_and_wide_rows(seed):
         else:
             qs = rng.standard_normal((3, D)).astype(np.float32) if batch == 1 else None
             T.full_round_trip_check(x, qs, offset=off, tag=tag)
+
+
+@pytest.mark.parametrize("seed", [20, 21])
+def test_random_shapes_attention_score_error(seed):
+    """Both forms of the score error on random (tokens, channels, queries, misalignment): rows that are a
+    multiple of 128 channels on aligned buffers take the bf16 matrix-core kernels (one or two query tiles per
+    workgroup, 32- or 64-token tiles, one to many tiles per workgroup), everything else the fp32 ones."""
+    rng = np.random.default_rng(seed)
+    for case in range(40):
+        D = int(rng.choice([128, 128, 256, 384, 512, 640, 1024, 2048, 100, 130, 64]))
+        Q = int(rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 65, 100, 140]))
+        N = int(rng.integers(1, max(2, min(40000, 300_000_000 // (D * Q)))))
+        off = int(rng.choice([0, 0, 0, 4, 1, 8]))
+        tag = "seed %d case %d: N %d D %d Q %d offset %d" % (seed, case, N, D, Q, off)
+        print(tag, flush=True)
+        x = T.make_matrix(rng, 1, N, D)
+        qs = (rng.standard_normal((Q, D)) * np.exp(rng.uniform(-2, 2, (Q, 1)))).astype(np.float32)
+        g = T.Gpu(x, offset=off)
+        s_ref = oracle.compute_scales(x)
+        q_ref = oracle.quantize(x, s_ref)
+        xh_ref = oracle.dequantize(q_ref, s_ref)
+        g.set_scales(s_ref)
+        g.codes.copy_(T.torch.from_numpy(q_ref.reshape(-1)))
+        g.xh.copy_(T.torch.from_numpy(xh_ref.reshape(-1)))
+        a_ref = oracle.attn_score_error(qs, x[0], xh_ref[0])
+        bound = T.attn_error_bound(qs, x[0], xh_ref[0])
+        for from_codes in (False, True):
+            a = g.attn_score_error(qs, from_codes)
+            assert a == pytest.approx(a_ref, rel=T.REL, abs=0), tag + " from_codes=%s" % from_codes
+            assert abs(a - a_ref) <= bound + 1e-13 * a_ref, tag + " beyond its rounding bound"
+        assert g.guards_intact(), tag
