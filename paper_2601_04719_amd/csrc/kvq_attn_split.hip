@@ -163,7 +163,7 @@ __global__ __launch_bounds__(2 * kBlock, 1) void attn_split_kernel(const void* _
   auto next_chunk = [&](uint32_t c) { return c + 1 == nchunks ? 0u : c + 1; };
   // Workgroups start their sweep over the channels at different chunks, so that they do not all ask for
   // the same lines of the queries at the same moment (the order of the chunks does not matter to the sum).
-  auto first_chunk = [&](uint32_t tile) { return (tile / qchunks) * 5u % nchunks; };
+  auto first_chunk = [&](uint32_t tile) { return (uint32_t)((uint64_t)(tile / qchunks) * 5u % nchunks); };
   double total = 0.0;
 
   if (wave >= 4) {
