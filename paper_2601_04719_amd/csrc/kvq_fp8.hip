@@ -119,7 +119,8 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_fp8_kernel(const uint8_t
       constexpr int R = decltype(nrows_tag)::value;
       uint32_t w[R];
 #pragma unroll
-      for (int u = 0; u < R; u++) w[u] = ld<NT>(reinterpret_cast<const uint32_t*>(pc + u * step));
+      // codes without the streaming hint, as in dequantize_kernel: they may stay in the memory-side cache
+      for (int u = 0; u < R; u++) w[u] = ld<false>(reinterpret_cast<const uint32_t*>(pc + u * step));
 #pragma unroll
       for (int u = 0; u < R; u++) {
         const f32x4 o = {dq8(w[u], 0, s[0]), dq8(w[u], 1, s[1]), dq8(w[u], 2, s[2]), dq8(w[u], 3, s[3])};

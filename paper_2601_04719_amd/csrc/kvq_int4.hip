@@ -89,7 +89,8 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize_int4_kernel(const uint8_
     constexpr int R = decltype(nrows_tag)::value;
     uint16_t w[R];
 #pragma unroll
-    for (int u = 0; u < R; u++) w[u] = ld<NT>(reinterpret_cast<const uint16_t*>(pc + u * pstep));
+    // codes without the streaming hint, as in dequantize_kernel: they may stay in the memory-side cache
+    for (int u = 0; u < R; u++) w[u] = ld<false>(reinterpret_cast<const uint16_t*>(pc + u * pstep));
 #pragma unroll
     for (int u = 0; u < R; u++) {
       f32x4 o;

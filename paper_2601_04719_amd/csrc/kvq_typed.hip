@@ -221,7 +221,8 @@ __global__ __launch_bounds__(kMaxBlock) void dequantize16_kernel(const int8_t* _
       constexpr int R = decltype(tag)::value;
       u32x2 c[R];
 #pragma unroll
-      for (int u = 0; u < R; u++) c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(pc + u * step));
+      // codes without the streaming hint, as in dequantize_kernel: they may stay in the memory-side cache
+      for (int u = 0; u < R; u++) c[u] = *reinterpret_cast<const u32x2*>(pc + u * step);
 #pragma unroll
       for (int u = 0; u < R; u++) {
         u16x8 o;
