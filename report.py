@@ -8,6 +8,7 @@ Usage:  python report.py [--configs 1,2,3,4,5] [--iters 20]
         python report.py --fp8              (FP8 E4M3 codes)
         python report.py --scores-int4      (attention scores straight from a 4-bit cache)
         python report.py --scores           (attention scores straight from int8 codes)
+        python report.py --attn             (attention-score error over shapes and query counts)
         python report.py --fused            (kvq_quantize_fused against the two calls, by column-tile width;
                                              with --calibration-copy a plain copy of known size is appended
                                              for scaling rocprofv3 --pmc counters)
@@ -37,6 +38,7 @@ def main():
     ap.add_argument("--scores-int4", action="store_true", help="kvq_scores_from_codes_int4 on decode-like shapes")
     ap.add_argument("--scores", action="store_true", help="kvq_scores_from_codes on decode-like shapes")
     ap.add_argument("--fused", action="store_true", help="kvq_quantize_fused by column-tile width vs two passes")
+    ap.add_argument("--attn", action="store_true", help="kvq_attn_score_error over shapes and query counts, both forms")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="with --fused: end with one plain 512 MiB device copy (known traffic for --pmc scaling)")
     args = ap.parse_args()
@@ -325,6 +327,37 @@ def main():
                     B, N, D, Q, kind, m, nbytes / 1e9, nbytes / m / 1e6, nbytes / m / 1e6 / 8000.0, 2.0 * Q * E / m / 1e9))
                 sys.stdout.flush()
             del codes
+            torch.cuda.empty_cache()
+        return
+
+    if args.attn:
+        print("| N x D | Q | form | (k, k_hat) ms | of 8 TB/s at 8 B/element | (k, codes) ms | of 8 TB/s at 5 B/element | fp32 matrix cores, (k, k_hat) ms |")
+        print("|---|---|---|---|---|---|---|---|")
+        mean = torch.zeros(1, dtype=torch.float64, device="cuda")
+        saved = kvq.kvq_get_option(kvq.OPT_ATTN_FORM)
+        for (N, D) in [(16384, 8192), (131072, 8192), (4096, 8192), (65536, 2048), (65536, 1024), (262144, 256),
+                       (1048576, 128), (32768, 128), (16384, 8200)]:
+            E = N * D
+            x = torch.randn(E, device="cuda")
+            scales = torch.empty(D, device="cuda")
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            xh = torch.empty(E, device="cuda")
+            kvq.kvq_absmax_scales(x, scales, 1, N, D)
+            kvq.kvq_quantize(x, scales, codes, 1, N, D)
+            kvq.kvq_dequantize(codes, scales, xh, 1, N, D)
+            for Q in (16, 64, 128):
+                q = torch.randn(Q * D, device="cuda")
+                kvq.kvq_set_option(kvq.OPT_ATTN_FORM, 0)
+                m1, _ = timeit(lambda: kvq.kvq_attn_score_error(q, Q, x, xh, None, None, N, D, mean))
+                m2, _ = timeit(lambda: kvq.kvq_attn_score_error(q, Q, x, None, codes, scales, N, D, mean))
+                kvq.kvq_set_option(kvq.OPT_ATTN_FORM, 1)
+                m3, _ = timeit(lambda: kvq.kvq_attn_score_error(q, Q, x, xh, None, None, N, D, mean))
+                kvq.kvq_set_option(kvq.OPT_ATTN_FORM, saved)
+                form = "bf16 pieces" if D % 128 == 0 else "fp32"
+                print("| %d x %d | %d | %s | %.4f | %.3f | %.4f | %.3f | %.4f |" % (
+                    N, D, Q, form, m1, 8.0 * E / m1 / 8e9, m2, 5.0 * E / m2 / 8e9, m3))
+                sys.stdout.flush()
+            del x, codes, xh
             torch.cuda.empty_cache()
         return
 
