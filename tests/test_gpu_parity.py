@@ -337,6 +337,42 @@ def test_attn_score_error_on_the_bf16_matrix_cores(N, D, Q):
         kvq.kvq_set_option(kvq.OPT_ATTN_FORM, saved)
 
 
+def test_attn_score_error_single_scores_stay_within_the_rounding_bound():
+    """One token and one query make the mean a single |score|, so the per-score bound can be held against the
+    hardware directly: 300 random rows of 128-2048 channels with magnitudes spread over 2^-20 .. 2^20, all
+    products of one sign (nothing cancels: the sum of magnitudes is the score) or of random sign, on the bf16
+    matrix cores and on the fp32 ones.  The bound allows two units in the last place per 16-product matrix
+    instruction; what is observed is printed."""
+    rng = np.random.default_rng(seed_of("single scores"))
+    saved = kvq.kvq_get_option(kvq.OPT_ATTN_FORM)
+    worst = {0: 0.0, 1: 0.0}
+    try:
+        for case in range(300):
+            D = int(rng.choice([128, 256, 512, 1024, 2048]))
+            k = (rng.standard_normal((1, D)) * np.exp2(rng.uniform(-20, 20, (1, D)))).astype(np.float32)
+            # a reconstruction a little off, as after quantization: k_hat = k (1 + up to 2^-8), rounded to fp32
+            kh = (k.astype(np.float64) * (1.0 + rng.uniform(-1, 1, (1, D)) * 2.0 ** -8)).astype(np.float32)
+            e = k.astype(np.float64) - kh.astype(np.float64)        # exact: k_hat is within a factor of two of k
+            q = (rng.standard_normal((1, D)) * np.exp2(rng.uniform(-10, 10, (1, D)))).astype(np.float32)
+            if case % 2 == 0:
+                q = (np.abs(q) * np.where(e[0] < 0, -1.0, 1.0)).astype(np.float32)   # every product >= 0
+            exact = abs(float((q.astype(np.float64) * e).sum()))
+            mags = float(np.abs(q.astype(np.float64) * e).sum())
+            g = Gpu(k)
+            g.xh.copy_(torch.from_numpy(kh.reshape(-1)))
+            for form in (0, 1):
+                kvq.kvq_set_option(kvq.OPT_ATTN_FORM, form)
+                got = g.attn_score_error(q, from_codes=False)
+                err = abs(got - exact)
+                assert err <= 65 * 2.0 ** -24 * mags, "case %d D %d form %d: off by %.3g of the sum of magnitudes" % (
+                    case, D, form, err / mags)
+                worst[form] = max(worst[form], err / mags)
+    finally:
+        kvq.kvq_set_option(kvq.OPT_ATTN_FORM, saved)
+    print("largest |gpu - exact| / sum of magnitudes: bf16 form %.2f x 2^-24, fp32 form %.2f x 2^-24"
+          % (worst[0] * 2.0 ** 24, worst[1] * 2.0 ** 24))
+
+
 # ------------------------------------------------------------------ shapes, tails, alignment
 def make_matrix(rng, batch, N, D):
     x = (rng.standard_normal((batch, N, D)) * np.exp(rng.uniform(-2, 2, (batch, 1, D)))).astype(np.float32)
