@@ -181,21 +181,24 @@ __global__ __launch_bounds__(kBlock) void scores_mfma_kernel(const float* __rest
   }
 }
 
-// Rows wider than 1024 channels (up to 8192): four queries per pass, their digits for the whole row
-// resident in 128 KiB of LDS, one workgroup of 16 wavefronts per compute unit.  Wavefront w prepares
-// quarter w / 4 of query w % 4; the token loop is the one above with a runtime number of steps.
+// Rows wider than 1024 channels (up to 8192): the digits of 4 G queries for the whole row resident in
+// 128 KiB of LDS -- G = 1 group of four queries per pass over the codes for rows of up to 8192 channels,
+// 2 up to 4096, 4 up to 2048 -- one workgroup of 16 wavefronts per compute unit.  Wavefront w prepares
+// quarter w / 4 of query w % 4 of every group; the token loop is the one above with a runtime number of
+// steps.
 constexpr int kWideBlock = 1024;
 constexpr int kWideMaxD = 8192;
 
+template <int G>
 __global__ __launch_bounds__(kWideBlock) void scores_mfma_wide_kernel(const float* __restrict__ queries,
                                                                       const int8_t* __restrict__ codes,
                                                                       const float* __restrict__ scales,
                                                                       float* __restrict__ out, int64_t N, int64_t D,
                                                                       int64_t q_total, int64_t q_first, int q_count,
                                                                       uint32_t chunks, int64_t tokens_per_chunk) {
-  __shared__ __align__(16) unsigned char dig[kWideMaxD * 16];  // [steps][64 lanes][16 bytes]
-  __shared__ double qscale[4];
-  __shared__ float red[16];
+  __shared__ __align__(16) unsigned char dig[kWideMaxD * 16];  // [steps][G][64 lanes][16 bytes], G * D <= 8192
+  __shared__ double qscale[4 * G];
+  __shared__ float red[G][16];
   const int steps = (int)(D >> 6);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -208,32 +211,40 @@ __global__ __launch_bounds__(kWideBlock) void scores_mfma_wide_kernel(const floa
   const float* qb = queries + (slab * q_total + q_first) * D;
 
   {
-    const int qi = wave & 3;
-    const bool live = qi < q_count;
     const int64_t d_lo = (int64_t)(wave >> 2) * (D >> 2), d_hi = d_lo + (D >> 2);
-    float m = 0.0f;
-    if (live)
-      for (int64_t d = d_lo + lane; d < d_hi; d += 64) m = fmaxf(m, fabsf(qb[qi * D + d] * ss[d]));
+    float m[G];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if (lane == 0) red[wave] = m;
+    for (int g = 0; g < G; g++) {
+      const int qi = 4 * g + (wave & 3);
+      m[g] = 0.0f;
+      if (qi < q_count)
+        for (int64_t d = d_lo + lane; d < d_hi; d += 64) m[g] = fmaxf(m[g], fabsf(qb[qi * D + d] * ss[d]));
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) m[g] = fmaxf(m[g], __shfl_xor(m[g], o));
+      if (lane == 0) red[g][wave] = m[g];
+    }
     __syncthreads();
-    m = fmaxf(fmaxf(red[qi], red[qi + 4]), fmaxf(red[qi + 8], red[qi + 12]));
-    int E = 0;
-    (void)frexpf(m, &E);
-    const double up = ldexp(1.0, 27 - E);
-    if (wave < 4 && lane == 0) qscale[qi] = ldexp(1.0, E - 27);
-    for (int64_t d = d_lo + lane; d < d_hi; d += 64) {
-      int I = 0;
-      if (live) I = (int)rint((double)(qb[qi * D + d] * ss[d]) * up);
-      const int s = (int)(d >> 6), h = (int)(d >> 4) & 3, b = (int)d & 15;
-      unsigned char* p = dig + ((size_t)s * 64 + 16 * h + 4 * qi) * 16 + b;
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const int pj = ((I + 64) & 127) - 64;
-        const int dj = j < 3 ? pj : I;
-        p[16 * j] = (unsigned char)(dj & 0xff);
-        I = (I - pj) >> 7;
+    for (int g = 0; g < G; g++) {
+      const int q4 = wave & 3, qi = 4 * g + q4;
+      const bool live = qi < q_count;
+      const float mm = fmaxf(fmaxf(red[g][q4], red[g][q4 + 4]), fmaxf(red[g][q4 + 8], red[g][q4 + 12]));
+      int E = 0;
+      (void)frexpf(mm, &E);
+      const double up = ldexp(1.0, 27 - E);
+      if (wave < 4 && lane == 0) qscale[qi] = ldexp(1.0, E - 27);
+      for (int64_t d = d_lo + lane; d < d_hi; d += 64) {
+        int I = 0;
+        if (live) I = (int)rint((double)(qb[qi * D + d] * ss[d]) * up);
+        const int s = (int)(d >> 6), h = (int)(d >> 4) & 3, b = (int)d & 15;
+        unsigned char* p = dig + ((size_t)(s * G + g) * 64 + 16 * h + 4 * q4) * 16 + b;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const int pj = ((I + 64) & 127) - 64;
+          const int dj = j < 3 ? pj : I;
+          p[16 * j] = (unsigned char)(dj & 0xff);
+          I = (I - pj) >> 7;
+        }
       }
     }
   }
@@ -249,14 +260,15 @@ __global__ __launch_bounds__(kWideBlock) void scores_mfma_wide_kernel(const floa
   // tokens of a tile lie in different DRAM pages, and short visits would reopen them over and over.
   constexpr int TW = 2, SU = 4;
   for (int64_t t0 = t_begin + (int64_t)wave * (16 * TW); t0 < t_end; t0 += (kWideBlock / 64) * 16 * TW) {
-    v4i acc[TW];
+    v4i acc[TW][G];
     const int8_t* row[TW];
 #pragma unroll
     for (int u = 0; u < TW; u++) {
       int64_t t = t0 + TW * n + u;  // a lane's tiles are consecutive tokens
       if (t >= t_end) t = t_end - 1;
       row[u] = cs + t * D;
-      acc[u] = v4i{0, 0, 0, 0};
+#pragma unroll
+      for (int g = 0; g < G; g++) acc[u][g] = v4i{0, 0, 0, 0};
     }
     for (int s = 0; s < steps; s += SU) {  // steps is a multiple of 4: D % 256 == 0 on this path
       v4i bv[TW][SU];
@@ -265,29 +277,35 @@ __global__ __launch_bounds__(kWideBlock) void scores_mfma_wide_kernel(const floa
 #pragma unroll
         for (int k = 0; k < SU; k++) bv[u][k] = *reinterpret_cast<const v4i*>(row[u] + 64 * (s + k));
 #pragma unroll
-      for (int k = 0; k < SU; k++) {
-        const v4i av = a_lds[(s + k) * 64 + lane];
+      for (int k = 0; k < SU; k++)
 #pragma unroll
-        for (int u = 0; u < TW; u++) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[u][k], acc[u], 0, 0, 0);
-      }
+        for (int g = 0; g < G; g++) {
+          const v4i av = a_lds[((s + k) * G + g) * 64 + lane];
+#pragma unroll
+          for (int u = 0; u < TW; u++)
+            acc[u][g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[u][k], acc[u][g], 0, 0, 0);
+        }
     }
-    const int qi = h;
-    if (qi >= q_count) continue;
     const int64_t tl = t0 + TW * n;
-    float v[TW];
 #pragma unroll
-    for (int u = 0; u < TW; u++) {
-      const int64_t S = (int64_t)acc[u][0] + (int64_t)acc[u][1] * 128 + (int64_t)acc[u][2] * 16384 +
-                        (int64_t)acc[u][3] * 2097152;
-      v[u] = (float)((double)S * qscale[qi]);
-    }
-    float* po = os + qi * N + tl;
-    if (vec_store && tl + 2 <= t_end) {
-      __builtin_nontemporal_store(f32x2{v[0], v[1]}, reinterpret_cast<f32x2*>(po));
-    } else {
+    for (int g = 0; g < G; g++) {
+      const int qi = 4 * g + h;
+      if (qi >= q_count) continue;
+      float v[TW];
 #pragma unroll
-      for (int u = 0; u < TW; u++)
-        if (tl + u < t_end) po[u] = v[u];
+      for (int u = 0; u < TW; u++) {
+        const int64_t S = (int64_t)acc[u][g][0] + (int64_t)acc[u][g][1] * 128 + (int64_t)acc[u][g][2] * 16384 +
+                          (int64_t)acc[u][g][3] * 2097152;
+        v[u] = (float)((double)S * qscale[qi]);
+      }
+      float* po = os + qi * N + tl;
+      if (vec_store && tl + 2 <= t_end) {
+        __builtin_nontemporal_store(f32x2{v[0], v[1]}, reinterpret_cast<f32x2*>(po));
+      } else {
+#pragma unroll
+        for (int u = 0; u < TW; u++)
+          if (tl + u < t_end) po[u] = v[u];
+      }
     }
   }
 }
@@ -348,7 +366,8 @@ bool scores_mfma_applicable(const float* queries, int64_t Q, const int8_t* codes
   (void)queries;
   (void)scales;
   // 16-byte code loads of whole 64-channel steps; digits of 8-16 queries in 32 KiB of LDS up to 1024
-  // channels, of 4 queries in 128 KiB up to 8192 channels (quarters of a row must be whole 16-byte pieces)
+  // channels, of 4 / 8 / 16 queries in 128 KiB up to 8192 / 4096 / 2048 channels (quarters of a row must be whole
+  // 16-byte pieces)
   return Q >= 3 && D % 64 == 0 && (D <= 1024 || (D % 256 == 0 && D <= kWideMaxD)) && aligned(codes, 16);
 }
 
@@ -363,10 +382,20 @@ kvq_status launch_scores_mfma(const float* queries, int64_t Q, const int8_t* cod
     per = (per + pass - 1) / pass * pass;
     const int64_t chunks = (N + per - 1) / per;
     if (batch * chunks > INT32_MAX) return KVQ_ERR_OVERFLOW;
-    for (int64_t q0 = 0; q0 < Q; q0 += 4) {
-      const int qc = (int)(Q - q0 < 4 ? Q - q0 : 4);
-      hipLaunchKernelGGL(scores_mfma_wide_kernel, dim3((uint32_t)(batch * chunks)), dim3(kWideBlock), 0, stream, queries,
-                         codes, scales, out, N, D, Q, q0, qc, (uint32_t)chunks, per);
+    // groups of four queries per pass: as many as keep the digits of a whole row within the 128 KiB
+    const int groups = D <= 2048 ? 4 : D <= 4096 ? 2 : 1;
+    const dim3 grid((uint32_t)(batch * chunks)), block(kWideBlock);
+    for (int64_t q0 = 0; q0 < Q; q0 += 4 * groups) {
+      const int qc = (int)(Q - q0 < 4 * groups ? Q - q0 : 4 * groups);
+      if (qc > 8)
+        hipLaunchKernelGGL(scores_mfma_wide_kernel<4>, grid, block, 0, stream, queries, codes, scales, out, N, D, Q, q0,
+                           qc, (uint32_t)chunks, per);
+      else if (qc > 4)
+        hipLaunchKernelGGL(scores_mfma_wide_kernel<2>, grid, block, 0, stream, queries, codes, scales, out, N, D, Q, q0,
+                           qc, (uint32_t)chunks, per);
+      else
+        hipLaunchKernelGGL(scores_mfma_wide_kernel<1>, grid, block, 0, stream, queries, codes, scales, out, N, D, Q, q0,
+                           qc, (uint32_t)chunks, per);
       KVQ_HIP(hipGetLastError());
     }
     return KVQ_OK;

@@ -313,7 +313,7 @@ def main():
         print("| batch x N x D | Q | kernel | mean ms | bytes moved (GB) | GB/s | of 8 TB/s | 2*Q*elements / time (Tflop/s) |")
         print("|---|---|---|---|---|---|---|---|")
         for (B, N, D) in [(256, 4096, 128), (2048, 4096, 128), (32, 131072, 128), (1, 1048576, 128), (4096, 4096, 64),
-                          (512, 4096, 256), (1, 131072, 8192)]:
+                          (512, 4096, 256), (1, 131072, 2048), (1, 131072, 4096), (1, 131072, 8192)]:
             E = B * N * D
             codes = torch.randint(-127, 128, (E,), dtype=torch.int8, device="cuda")
             scales = torch.rand(B * D, device="cuda") + 0.1

@@ -506,7 +506,10 @@ def check_scores(x, qs, Q, offset=0):
 @pytest.mark.parametrize("shape,Q", [((1, 1024, 64), 16), ((1, 4096, 128), 1), ((6, 1000, 128), 8), ((3, 257, 128), 5),
                                      ((1, 300, 80), 3), ((2, 100, 1024), 2), ((1, 50, 4096), 9), ((1, 33, 100), 4),
                                      ((2, 1, 16), 1), ((1, 70, 20), 2), ((2, 700, 256), 4), ((1, 300, 2048), 3), ((1, 300, 1024), 3), ((2, 64, 192), 8),
-                                     ((4, 33, 64), 7), ((1, 5000, 128), 13), ((3, 1, 128), 8)],
+                                     ((4, 33, 64), 7), ((1, 5000, 128), 13), ((3, 1, 128), 8),
+                                     # rows of 1280-8192 channels: 16 / 8 / 4 queries per pass, whole and partial groups
+                                     ((1, 300, 2048), 16), ((2, 77, 2048), 11), ((1, 40, 4096), 6), ((1, 33, 8192), 7),
+                                     ((1, 100, 1280), 13), ((1, 2100, 4096), 8)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else "Q%d" % v)
 def test_scores_from_codes(shape, Q):
     batch, N, D = shape
