@@ -284,7 +284,8 @@ kvq_status kvq_append(const float* x_new, float* scales, float* scales_prev, int
 kvq_status kvq_prepare_stream(kvq_stream_t stream) {
   Workspace ws;
   if (kvq_status s = get_workspace(stream, &ws)) return s;
-  return prepare_attn_split();
+  if (kvq_status s = prepare_attn_split()) return s;
+  return prepare_fused_tall();
 }
 
 kvq_status kvq_release_stream(kvq_stream_t stream) { return release_workspace(stream); }
@@ -321,6 +322,7 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
   // column before its first code can be written, i.e. two passes over x.  (Splitting the batch into
   // groups small enough for the 256 MiB memory-side cache was measured and gave no reuse.)
   if (fused_slab_applicable(x, scales, codes, N, D)) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
+  if (fused_tall_applicable(x, scales, codes, N, D)) return launch_fused_tall(x, scales, codes, batch, N, D, stream);
   if (kvq_status s = launch_absmax_scales(x, scales, batch, N, D, stream)) return s;
   return launch_quantize(x, scales, codes, batch, N, D, stream);
 }

@@ -197,6 +197,10 @@ kvq_status kvq_set_option(int key, int value) {
       if (value != 0 && value != 1) return KVQ_ERR_ARG;
       o.attn_form = value;
       return KVQ_OK;
+    case KVQ_OPT_FUSED_TALL:
+      if (value != 0 && value != 1) return KVQ_ERR_ARG;
+      o.fused_tall = value;
+      return KVQ_OK;
     default:
       return KVQ_ERR_ARG;
   }
@@ -219,6 +223,7 @@ int kvq_get_option(int key) {
     case KVQ_OPT_FUSED_MIN_LANES: return o.fused_min_lanes;
     case KVQ_OPT_FUSED_MAX_ROWS: return o.fused_max_rows;
     case KVQ_OPT_ATTN_FORM: return o.attn_form;
+    case KVQ_OPT_FUSED_TALL: return o.fused_tall;
     default: return INT_MIN;
   }
 }

@@ -1,0 +1,287 @@
+// Scale computation and quantization in one pass for slabs of 2049 to 4096 rows
+// (paper: Eq. (scale_compute) + Eq. (quant_op); same results as the two separate kernels).
+//
+// The single pass has to hold all N rows of the columns it works on.  Up to N = 2048 a column tile of
+// 32 channels (one 128-byte line of x per row) fits the registers of a workgroup (kvq_fused.hip).  At
+// N = 4096 such a tile is 512 KiB, the whole register file of a compute unit, so here one 512-lane
+// workgroup owns the unit: each lane keeps 46 rows of 4 channels in registers (184 of its 256) and 18 more
+// in a private slot of LDS (144 KiB in all).  With a single workgroup per unit nothing else hides the
+// phases of a tile behind each other, so the workgroup is persistent and pipelines them itself: while it
+// quantizes and stores the rows of one tile, register by register, it issues the loads of the next tile
+// into the registers just freed.  Only the reduction of the column maxima (three lane exchanges, one
+// barrier) runs with nothing in flight.
+//
+// All loads and stores go through buffer descriptors sized to the tile, so rows past N, channels past D
+// and the tile after a workgroup's last one need no branches: loads beyond the descriptor return zero
+// (which leaves a maximum of absolute values alone) and stores beyond it are dropped.
+#include <atomic>
+#include <type_traits>
+#include <utility>
+
+#include "kvq_internal.h"
+
+namespace kvq {
+
+namespace {
+
+constexpr int kTallBlock = 512;   // lanes: 8 along a row (32 channels) x 64 down the rows
+constexpr int kTallTX = 8, kTallTY = kTallBlock / kTallTX;
+constexpr int kTallRegRows = 46;  // rows per lane held in registers
+constexpr int kTallLdsRows = 18;  // rows per lane held in LDS
+constexpr int kTallBatches = 6;   // a tile's rows are worked through in this many batches
+constexpr int kTallStage = (kTallLdsRows + kTallBatches - 1) / kTallBatches;  // rows staged on their way to LDS
+constexpr int kTallRows = kTallTY * (kTallRegRows + kTallLdsRows);  // 4096
+constexpr int kTallWaves = kTallBlock / 64;
+constexpr size_t kTallLdsBytes =
+    (size_t)kTallLdsRows * kTallBlock * 16 + 2 * (size_t)kTallWaves * kTallTX * 16;
+static_assert(kTallLdsBytes <= 160 * 1024, "LDS of one compute unit");
+constexpr int kTallXcds = 8;              // workgroup i of a launch is handed to XCD i % 8
+constexpr uint32_t kOutside = 0x80000000u;  // an offset no descriptor reaches, whatever is added below 2^31
+
+template <int... I, typename F>
+__device__ __forceinline__ void tall_unroll_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void tall_unroll(F&& f) {
+  tall_unroll_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// A descriptor is the same for every lane; saying so keeps it in scalar registers across the loop.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tall_buffer(const void* base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(lo | hi << 32), 0,
+                                           __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
+}
+
+// Where a workgroup is in the sequence of tiles of its XCD.  Quads of adjacent column tiles (which share
+// lines of codes) are dealt to the XCDs in turn, and the tiles of a quad are neighbours in an XCD's
+// sequence, so they are in flight on compute units of the same XCD at the same time and their pieces of a
+// line meet in its L2.  A workgroup keeps its place inside a quad and walks from quad to quad in steps the
+// host has already divided into whole slabs and a rest, so the walk needs scalar additions only.
+struct TallTile {
+  uint32_t quad;         // number of the quad, slab-major; >= total_quads: no tile
+  uint32_t slab;         // quad / quads_per_slab
+  uint32_t quad_in_slab;  // quad % quads_per_slab
+};
+
+__global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* __restrict__ x,
+                                                                   float* __restrict__ scales,
+                                                                   int8_t* __restrict__ codes, uint32_t total_quads,
+                                                                   uint32_t quads_per_slab, uint32_t quad_log2,
+                                                                   uint32_t step_slabs, uint32_t step_quads,
+                                                                   uint32_t N, uint32_t D) {
+  extern __shared__ __align__(16) unsigned char tall_lds[];
+  f32x4* const rows = reinterpret_cast<f32x4*>(tall_lds);       // [kTallLdsRows][kTallBlock], slot per lane
+  f32x4* const red = rows + kTallLdsRows * kTallBlock;          // [2][kTallWaves][kTallTX]
+  const uint32_t tid = threadIdx.x, tx = tid % kTallTX, ty = tid / kTallTX, wave = tid / 64, lane = tid % 64;
+  const uint32_t xcd = blockIdx.x % kTallXcds, first = blockIdx.x / kTallXcds;
+  const uint32_t column_tile = first & ((1u << quad_log2) - 1);  // this workgroup's place in every quad
+  const uint32_t xstep = kTallTY * D * 4, cstep = kTallTY * D;  // bytes from a lane's row to its next one
+  const int64_t slab_elems = (int64_t)N * D;
+
+  f32x4 v[kTallRegRows];
+  float m[4];
+  float div[4];
+
+  // Loads a tile (descriptor nx, this lane's first byte xo) while quantizing the tile held in v and LDS
+  // into the codes behind cx at this lane's first byte co.  Leaves the column maxima of the loaded
+  // rows in m.  In kTallBatches batches: a batch first quantizes its share of the rows held in LDS, which
+  // frees their slots; moves the rows the batch before loaded for those slots from the staging registers
+  // to LDS; loads its own rows for LDS into the staging registers; then quantizes its share of the rows
+  // held in registers, loading the next tile's row into each register as it is freed.  Loads return in
+  // order, so waiting for the staged rows of the batch before leaves everything younger in flight.
+  auto turn = [&](__amdgpu_buffer_rsrc_t cx, uint32_t co, __amdgpu_buffer_rsrc_t nx, uint32_t xo) {
+    auto encode = [&](const f32x4& r) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        float y = r[i] / div[i];
+        y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
+        w |= (__float_as_uint(y + kRoundMagic) & 0xffu) << (8 * i);
+      }
+      return w;
+    };
+    auto fetch = [&](int row) {
+      const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(nx, (int)(xo + (uint32_t)row * xstep), 0, 2);
+      return __builtin_bit_cast(f32x4, w);
+    };
+    auto put = [&](const f32x4& r, int row) {
+      __builtin_amdgcn_raw_buffer_store_b32(encode(r), cx, (int)(co + (uint32_t)row * cstep), 0, 0);
+    };
+    f32x4 staged[kTallStage];
+#pragma unroll
+    for (int i = 0; i < 4; i++) m[i] = 0.0f;
+    auto hand_over = [&](auto B) {  // the staged rows of batch B: into the maxima and to their slots in LDS
+      tall_unroll<kTallStage>([&](auto J) {
+        constexpr int j = decltype(B)::value * kTallStage + decltype(J)::value;
+        if constexpr (j < kTallLdsRows) {
+#pragma unroll
+          for (int i = 0; i < 4; i++) m[i] = fmaxf(m[i], fabsf(staged[decltype(J)::value][i]));
+          rows[j * kTallBlock + tid] = staged[decltype(J)::value];
+        }
+      });
+      // maxima may be taken in any order, and the compiler would rather take them all at the end and keep
+      // the staged rows until then: have these here and now
+      asm volatile("" : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]));
+    };
+    tall_unroll<kTallBatches>([&](auto B) {
+      constexpr int b = decltype(B)::value;
+      tall_unroll<kTallStage>([&](auto J) {
+        constexpr int j = b * kTallStage + decltype(J)::value;
+        if constexpr (j < kTallLdsRows) put(rows[j * kTallBlock + tid], kTallRegRows + j);
+      });
+      // the fences keep the steps in this order: left alone, the compiler moves the hand-over to right
+      // behind the staging loads and waits for them with little else in flight
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (b > 0) hand_over(std::integral_constant<int, (b > 0 ? b - 1 : 0)>{});
+      __builtin_amdgcn_sched_barrier(0);
+      tall_unroll<kTallStage>([&](auto J) {
+        constexpr int j = b * kTallStage + decltype(J)::value;
+        if constexpr (j < kTallLdsRows) staged[decltype(J)::value] = fetch(kTallRegRows + j);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int lo = b * kTallRegRows / kTallBatches, hi = (b + 1) * kTallRegRows / kTallBatches;
+      tall_unroll<hi - lo>([&](auto U) {
+        constexpr int u = lo + decltype(U)::value;
+        put(v[u], u);
+        v[u] = fetch(u);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    hand_over(std::integral_constant<int, kTallBatches - 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    tall_unroll<kTallRegRows>([&](auto U) {
+      constexpr int u = decltype(U)::value;
+#pragma unroll
+      for (int i = 0; i < 4; i++) m[i] = fmaxf(m[i], fabsf(v[u][i]));
+    });
+  };
+
+  // first channel and width (0: no such tile) of the workgroup's tile of a quad; descriptors of its x and codes
+  auto first_channel_of = [&](const TallTile& t) {
+    return ((t.quad_in_slab << quad_log2) + column_tile) * (kTallTX * 4);
+  };
+  auto width_of = [&](const TallTile& t) {
+    const uint32_t c = first_channel_of(t);
+    if (t.quad >= total_quads || c >= D) return 0u;
+    return D - c < kTallTX * 4 ? D - c : (uint32_t)(kTallTX * 4);
+  };
+  auto x_of = [&](const TallTile& t) {
+    const uint32_t w = width_of(t);
+    return tall_buffer(x + t.slab * slab_elems + first_channel_of(t), w ? ((N - 1) * D + w) * 4 : 0);
+  };
+  auto codes_of = [&](const TallTile& t) {
+    const uint32_t w = width_of(t);
+    return tall_buffer(codes + t.slab * slab_elems + first_channel_of(t), w ? (N - 1) * D + w : 0);
+  };
+
+  // One turn more than the workgroup has tiles: the first quantizes nothing (an empty descriptor drops its
+  // stores) and loads the first tile, the last loads nothing and quantizes the last tile.
+  TallTile cur{total_quads, 0, 0};
+  TallTile nxt;
+  nxt.quad = xcd + kTallXcds * (first >> quad_log2);
+  nxt.slab = (uint32_t)__builtin_amdgcn_readfirstlane((int)(nxt.quad / quads_per_slab));
+  nxt.quad_in_slab = nxt.quad - nxt.slab * quads_per_slab;
+#pragma unroll
+  for (int u = 0; u < kTallRegRows; u++) v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int i = 0; i < 4; i++) div[i] = 1.0f;
+  uint32_t parity = 0;
+  for (;;) {
+    const uint32_t cw = width_of(cur), nw = width_of(nxt);
+    const uint32_t co = tx * 4 < cw ? ty * D + tx * 4 : kOutside;
+    const uint32_t xo = tx * 4 < nw ? ty * D * 4 + tx * 16 : kOutside;
+    turn(codes_of(cur), co, x_of(nxt), xo);
+    if (nxt.quad >= total_quads) break;  // nothing was loaded: the tile just written was the last (same for all lanes)
+    cur = nxt;
+    nxt.quad += step_slabs * quads_per_slab + step_quads;
+    nxt.slab += step_slabs;
+    nxt.quad_in_slab += step_quads;
+    if (nxt.quad_in_slab >= quads_per_slab) {
+      nxt.quad_in_slab -= quads_per_slab;
+      nxt.slab += 1;
+    }
+
+    // column maxima: over the 8 lanes of a wavefront that share a column group, then over the wavefronts
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      m[i] = fmaxf(m[i], __shfl_xor(m[i], 8));
+      m[i] = fmaxf(m[i], __shfl_xor(m[i], 16));
+      m[i] = fmaxf(m[i], __shfl_xor(m[i], 32));
+    }
+    f32x4* const slot = red + parity * (kTallWaves * kTallTX);
+    if (lane < kTallTX) slot[wave * kTallTX + lane] = f32x4{m[0], m[1], m[2], m[3]};
+    __syncthreads();
+    f32x4 top = slot[tx];
+#pragma unroll
+    for (int w = 1; w < kTallWaves; w++) {
+      const f32x4 o = slot[w * kTallTX + tx];
+#pragma unroll
+      for (int i = 0; i < 4; i++) top[i] = fmaxf(top[i], o[i]);
+    }
+    parity ^= 1;  // the next tile's maxima go to the other half, so one barrier per tile is enough
+    f32x4 sc;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      sc[i] = top[i] / 127.0f;  // the one IEEE divide per channel
+      div[i] = divisor_of(sc[i]);
+    }
+    if (tx * 4 < width_of(cur) && ty == 0)
+      *reinterpret_cast<f32x4*>(scales + (int64_t)cur.slab * D + first_channel_of(cur) + tx * 4) = sc;
+  }
+}
+
+}  // namespace
+
+// The kernel asks for more dynamic LDS than a kernel gets by default: raise its limit, once per device
+// (also from kvq_prepare_stream, so that nothing but launches is left for a stream capture).
+kvq_status prepare_fused_tall() {
+  static std::atomic<uint64_t> done{0};
+  int dev = -1;
+  KVQ_HIP(hipGetDevice(&dev));
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return KVQ_OK;
+  KVQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tall_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTallLdsBytes));
+  if (bit) done.fetch_or(bit, std::memory_order_release);
+  return KVQ_OK;
+}
+
+// Slabs taller than the register-only kernel reaches with 32-channel tiles, up to 4096 rows; every byte
+// offset inside a tile (up to 4096 rows of D floats, plus the marker for lanes outside) within 32 bits.
+bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D) {
+  if (options().fused_tall == 0) return false;
+  if (D % 4 || !aligned(x, 16) || !aligned(scales, 16) || !aligned(codes, 4)) return false;
+  return N > kTallRows / 2 && N <= kTallRows && D <= 65536;
+}
+
+kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
+                             hipStream_t stream) {
+  const DeviceInfo dev = current_device();
+  if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
+  if (kvq_status s = prepare_fused_tall()) return s;
+  const int64_t ctiles = (D + kTallTX * 4 - 1) / (kTallTX * 4);
+  const int quad_log2 = ctiles < 2 ? 0 : ctiles < 3 ? 1 : 2;  // four column tiles share a 128-byte line of codes
+  const int64_t quad_tiles = (int64_t)1 << quad_log2;
+  const int64_t quads_per_slab = (ctiles + quad_tiles - 1) / quad_tiles;
+  if (batch > INT32_MAX / (2 * kTallXcds) / quads_per_slab) return KVQ_ERR_OVERFLOW;
+  const int64_t total_quads = batch * quads_per_slab;
+  // one workgroup per compute unit, the same number on every XCD and whole quads of them, no more than the
+  // longest sequence has tiles; a workgroup then moves on by per_xcd / quad_tiles quads of its XCD a step
+  int64_t per_xcd = dev.cus / kTallXcds / quad_tiles * quad_tiles;
+  if (per_xcd < quad_tiles) per_xcd = quad_tiles;
+  const int64_t longest = (total_quads + kTallXcds - 1) / kTallXcds * quad_tiles;
+  if (per_xcd > longest) per_xcd = longest;
+  const int64_t step = kTallXcds * (per_xcd / quad_tiles);  // in quads, slab-major
+  hipLaunchKernelGGL(fused_tall_kernel, dim3((uint32_t)(per_xcd * kTallXcds)), dim3(kTallBlock), kTallLdsBytes,
+                     stream, x, scales, codes, (uint32_t)total_quads, (uint32_t)quads_per_slab, (uint32_t)quad_log2,
+                     (uint32_t)(step / quads_per_slab), (uint32_t)(step % quads_per_slab), (uint32_t)N,
+                     (uint32_t)D);
+  KVQ_HIP(hipGetLastError());
+  return KVQ_OK;
+}
+
+}  // namespace kvq

@@ -23,6 +23,7 @@ OPT_APPEND_BLOCKS_PER_CU = 12
 OPT_FUSED_MIN_LANES = 13
 OPT_FUSED_MAX_ROWS = 14
 OPT_ATTN_FORM = 15
+OPT_FUSED_TALL = 16
 
 # the method and its workspace calls: include/kvq.h
 EXPORTS = (

@@ -626,7 +626,10 @@ FUSED_SHAPES = [(7, 512, 128), (3, 1000, 64), (2, 16, 4096), (5, 17, 20), (1, 16
                 # slabs cut into column tiles of a few 16-byte groups, all rows in one workgroup: slab counts that
                 # do and do not fill the eight XCD queues, ragged row counts, tiles that overhang the last channel
                 (3, 4096, 128), (9, 3000, 64), (1, 2048, 256), (5, 1500, 1000), (2, 4, 8192), (10, 4096, 16),
-                (17, 4095, 20), (8, 1025, 136), (1, 4097, 128), (2, 700, 4100)]
+                (17, 4095, 20), (8, 1025, 136), (1, 4097, 128), (2, 700, 4100),
+                # 2049 to 4096 rows: a 32-channel column tile in the registers and LDS of a persistent workgroup;
+                # more tiles than workgroups, quads of tiles with empty places, one row past the register-only form
+                (70, 4096, 128), (33, 3100, 260), (1, 2049, 128), (2, 4096, 36), (5, 2500, 1000), (600, 2050, 8)]
 
 
 @pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -636,20 +639,25 @@ def test_single_pass_fused_slabs(shape):
     x = make_matrix(rng, *shape)
     s_ref = oracle.compute_scales(x)
     q_ref = oracle.quantize(x, s_ref)
-    saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS)
+    saved = (kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS),
+             kvq.kvq_get_option(kvq.OPT_FUSED_TALL))
     try:
-        # the defaults; the narrowest column tiles with every register depth; wide tiles only
-        for min_lanes, max_rows in (saved, (4, 16), (4, 8), (4, 4), (64, 0)):
+        # the defaults; the narrowest column tiles with every register depth; wide tiles only; and the same
+        # without the form for 2049 to 4096 rows (two passes there)
+        for min_lanes, max_rows, tall in (saved, (4, 16, 1), (4, 8, 1), (4, 4, 1), (64, 0, 1), (saved[0], saved[1], 0)):
             kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, min_lanes)
             kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, max_rows)
+            kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)
             g = Gpu(x)
             s_f, q_f = g.quantize_fused()
-            assert_bits_equal(s_f, s_ref, "fused scales (min lanes %d, rows %d)" % (min_lanes, max_rows))
-            assert_bits_equal(q_f, q_ref, "fused codes (min lanes %d, rows %d)" % (min_lanes, max_rows))
-            assert g.guards_intact()
+            what = "(min lanes %d, rows %d, tall %d)" % (min_lanes, max_rows, tall)
+            assert_bits_equal(s_f, s_ref, "fused scales " + what)
+            assert_bits_equal(q_f, q_ref, "fused codes " + what)
+            assert g.guards_intact(), "fused wrote outside its buffers " + what
     finally:
         kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved[0])
         kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, saved[1])
+        kvq.kvq_set_option(kvq.OPT_FUSED_TALL, saved[2])
 
 
 # ------------------------------------------------------------------ every launch shape, same bits
