@@ -134,11 +134,17 @@ kvq_status get_workspace(hipStream_t stream, Workspace* out) {
     return KVQ_OK;
   }
   void* p = nullptr;
-  KVQ_HIP(hipMalloc(&p, (size_t)kMaxPartials * (sizeof(double) + sizeof(float)) + (size_t)kColmaxFloats * sizeof(float)));
+  KVQ_HIP(hipMalloc(&p, (size_t)kMaxPartials * (sizeof(double) + sizeof(float)) + (size_t)kColmaxFloats * sizeof(float) +
+                            (size_t)kTickets * sizeof(uint32_t)));
   Workspace w;
   w.sums = static_cast<double*>(p);
   w.maxes = reinterpret_cast<float*>(w.sums + kMaxPartials);
   w.colmax = w.maxes + kMaxPartials;
+  w.tickets = reinterpret_cast<uint32_t*>(w.colmax + kColmaxFloats);
+  if (hipError_t e = hipMemsetAsync(w.tickets, 0, (size_t)kTickets * sizeof(uint32_t), stream)) {
+    (void)hipFree(p);
+    return hip_failed(e);
+  }
   g_ws_table[key] = w;
   *out = w;
   return KVQ_OK;
@@ -322,7 +328,11 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
   // column before its first code can be written, i.e. two passes over x.  (Splitting the batch into
   // groups small enough for the 256 MiB memory-side cache was measured and gave no reuse.)
   if (fused_slab_applicable(x, scales, codes, N, D)) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
-  if (fused_tall_applicable(x, scales, codes, N, D)) return launch_fused_tall(x, scales, codes, batch, N, D, stream);
+  if (fused_tall_applicable(x, scales, codes, N, D)) {
+    Workspace ws;
+    if (kvq_status s = get_workspace(stream, &ws)) return s;
+    return launch_fused_tall(x, scales, codes, batch, N, D, ws, stream);
+  }
   if (kvq_status s = launch_absmax_scales(x, scales, batch, N, D, stream)) return s;
   return launch_quantize(x, scales, codes, batch, N, D, stream);
 }

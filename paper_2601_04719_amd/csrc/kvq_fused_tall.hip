@@ -36,6 +36,7 @@ constexpr size_t kTallLdsBytes =
     (size_t)kTallLdsRows * kTallBlock * 16 + 2 * (size_t)kTallWaves * kTallTX * 16;
 static_assert(kTallLdsBytes <= 160 * 1024, "LDS of one compute unit");
 constexpr int kTallXcds = 8;              // workgroup i of a launch is handed to XCD i % 8
+constexpr int kTallPolls = 64;             // how often a workgroup looks for its neighbours before it goes on alone
 constexpr uint32_t kOutside = 0x80000000u;  // an offset no descriptor reaches, whatever is added below 2^31
 
 template <int... I, typename F>
@@ -72,7 +73,8 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
                                                                    int8_t* __restrict__ codes, uint32_t total_quads,
                                                                    uint32_t quads_per_slab, uint32_t quad_log2,
                                                                    uint32_t step_slabs, uint32_t step_quads,
-                                                                   uint32_t N, uint32_t D) {
+                                                                   uint32_t N, uint32_t D,
+                                                                   uint32_t* __restrict__ tickets) {
   extern __shared__ __align__(16) unsigned char tall_lds[];
   f32x4* const rows = reinterpret_cast<f32x4*>(tall_lds);       // [kTallLdsRows][kTallBlock], slot per lane
   f32x4* const red = rows + kTallLdsRows * kTallBlock;          // [2][kTallWaves][kTallTX]
@@ -189,6 +191,17 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
   for (int u = 0; u < kTallRegRows; u++) v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int i = 0; i < 4; i++) div[i] = 1.0f;
+  // The workgroups that hold the other tiles of the same quads (same XCD, same place in its sequence) write
+  // the other pieces of the same lines of codes.  The pieces only meet in L2 if they are written within a
+  // few microseconds of each other, and left alone the workgroups drift apart by more than that within a
+  // few tiles (a line that leaves L2 in pieces costs several times its share of the write bandwidth).  So
+  // before each tile's stores a workgroup takes a ticket from the quads' counter and waits, for a bounded
+  // number of polls, until its neighbours have taken theirs.  Nothing depends on the wait but speed: when
+  // the bound is reached the workgroup goes on.  After its last tile a workgroup takes one more ticket, and
+  // whoever takes the very last one puts the counter back to zero for the next launch.
+  uint32_t* const ticket = tickets ? tickets + (xcd * (gridDim.x / kTallXcds >> quad_log2) + (first >> quad_log2)) : nullptr;
+  const uint32_t neighbours = 1u << quad_log2;
+  uint32_t turns = 0;
   uint32_t parity = 0;
   for (;;) {
     const uint32_t cw = width_of(cur), nw = width_of(nxt);
@@ -196,6 +209,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
     const uint32_t xo = tx * 4 < nw ? ty * D * 4 + tx * 16 : kOutside;
     turn(codes_of(cur), co, x_of(nxt), xo);
     if (nxt.quad >= total_quads) break;  // nothing was loaded: the tile just written was the last (same for all lanes)
+    turns++;
     cur = nxt;
     nxt.quad += step_slabs * quads_per_slab + step_quads;
     nxt.slab += step_slabs;
@@ -231,6 +245,23 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
     }
     if (tx * 4 < width_of(cur) && ty == 0)
       *reinterpret_cast<f32x4*>(scales + (int64_t)cur.slab * D + first_channel_of(cur) + tx * 4) = sc;
+
+    if (ticket) {
+      if (tid == 0) {
+        const uint32_t all_here = turns * neighbours;
+        uint32_t seen = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+        for (int poll = 0; seen < all_here && poll < kTallPolls; poll++) {
+          __builtin_amdgcn_s_sleep(16);
+          seen = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (ticket && tid == 0 && turns > 0) {
+    const uint32_t last = (turns + 1) * neighbours - 1;
+    if (__hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == last)
+      __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -259,7 +290,7 @@ bool fused_tall_applicable(const float* x, const float* scales, const int8_t* co
 }
 
 kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
-                             hipStream_t stream) {
+                             const Workspace& ws, hipStream_t stream) {
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   if (kvq_status s = prepare_fused_tall()) return s;
@@ -276,10 +307,13 @@ kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64
   const int64_t longest = (total_quads + kTallXcds - 1) / kTallXcds * quad_tiles;
   if (per_xcd > longest) per_xcd = longest;
   const int64_t step = kTallXcds * (per_xcd / quad_tiles);  // in quads, slab-major
+  // a counter per group of neighbours; none where a quad is a single tile or the workspace has too few
+  uint32_t* const tickets =
+      options().fused_tall == 1 && quad_tiles > 1 && step <= kTickets ? ws.tickets : nullptr;
   hipLaunchKernelGGL(fused_tall_kernel, dim3((uint32_t)(per_xcd * kTallXcds)), dim3(kTallBlock), kTallLdsBytes,
                      stream, x, scales, codes, (uint32_t)total_quads, (uint32_t)quads_per_slab, (uint32_t)quad_log2,
                      (uint32_t)(step / quads_per_slab), (uint32_t)(step % quads_per_slab), (uint32_t)N,
-                     (uint32_t)D);
+                     (uint32_t)D, tickets);
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }

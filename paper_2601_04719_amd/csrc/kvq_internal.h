@@ -79,7 +79,7 @@ struct Options {
   int append_blocks_per_cu = 32;  // row chunking of the requantization pass of kvq_append
   int fused_min_lanes = 8;        // narrowest column tile of the single-pass fused kernel, in 16-byte lanes along a row
   int fused_max_rows = 0;         // rows a lane of that kernel holds: 4, 8, 16, or 0 = 8 where the tiles stay wide enough, else 16
-  int fused_tall = 1;             // slabs of 2049..4096 rows: 1 = the single-pass kernel that also keeps rows in LDS, 0 = two passes
+  int fused_tall = 1;             // slabs of 2049..4096 rows: 1 = the single-pass kernel that also keeps rows in LDS, 0 = two passes, 2 = as 1 but workgroups do not wait for their neighbours
   int attn_form = 0;              // score-error contraction: 0 = bf16 pieces where the shape allows, 1 = fp32 matrix cores always
 };
 Options& options();
@@ -112,10 +112,12 @@ int pick_width(int64_t D, const void* fp32_ptr, const void* int8_ptr, int want);
 // maxima of the scale reductions.
 constexpr int kMaxPartials = 8192;
 constexpr int64_t kColmaxFloats = (int64_t)1 << 22;  // 16 MiB
+constexpr int kTickets = 1024;
 struct Workspace {
   double* sums;   // [kMaxPartials]
   float* maxes;   // [kMaxPartials]
   float* colmax;  // [kColmaxFloats]: [row chunk][batch * D]
+  uint32_t* tickets;  // [kTickets]: zero between launches (each kernel that counts in them leaves them at zero)
 };
 kvq_status get_workspace(hipStream_t stream, Workspace* out);
 // frees the current device's workspace of `stream`, if there is one
@@ -174,7 +176,7 @@ bool fused_slab_applicable(const float* x, const float* scales, const int8_t* co
 bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D);
 kvq_status prepare_fused_tall();
 kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
-                             hipStream_t stream);
+                             const Workspace& ws, hipStream_t stream);
 kvq_status launch_fused_slab(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
                              hipStream_t stream);
 kvq_status launch_quantize_variant(int variant, const float* x, const float* scales, int8_t* codes,

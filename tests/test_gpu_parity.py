@@ -642,9 +642,10 @@ def test_single_pass_fused_slabs(shape):
     saved = (kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS),
              kvq.kvq_get_option(kvq.OPT_FUSED_TALL))
     try:
-        # the defaults; the narrowest column tiles with every register depth; wide tiles only; and the same
-        # without the form for 2049 to 4096 rows (two passes there)
-        for min_lanes, max_rows, tall in (saved, (4, 16, 1), (4, 8, 1), (4, 4, 1), (64, 0, 1), (saved[0], saved[1], 0)):
+        # the defaults; the narrowest column tiles with every register depth; wide tiles only; the form for
+        # 2049 to 4096 rows without its workgroups waiting for each other; and without that form (two passes)
+        for min_lanes, max_rows, tall in (saved, (4, 16, 1), (4, 8, 1), (4, 4, 1), (64, 0, 1), (saved[0], saved[1], 2),
+                                         (saved[0], saved[1], 0)):
             kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, min_lanes)
             kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, max_rows)
             kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)
@@ -1288,6 +1289,36 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     s_ref = oracle.compute_scales(xs[0])
     assert_bits_equal(g.scales.cpu().numpy().reshape(batch, D), s_ref, "scales after the last replay")
     assert_bits_equal(g.codes.cpu().numpy().reshape(batch, N, D), oracle.quantize(xs[0], s_ref), "codes after replay")
+
+
+def test_fused_call_on_tall_slabs_can_be_captured_and_replayed():
+    """kvq_quantize_fused on slabs of 2049 to 4096 rows: its workgroups count themselves in and out of a
+    few counters in the stream's workspace and leave them at zero, so the launch can be captured once and
+    replayed; more tiles than workgroups, so some take a second tile."""
+    rng = np.random.default_rng(6)
+    batch, N, D = 70, 2100, 128
+    xs = [make_matrix(rng, batch, N, D) for _ in range(2)]
+    g = Gpu(xs[0])
+    side = torch.cuda.Stream()
+    kvq.kvq_prepare_stream(side.cuda_stream)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        kvq.kvq_quantize_fused(g.x, g.scales, g.codes, batch, N, D)
+    for x_np in (xs[1], xs[0], xs[1]):
+        g.x.copy_(torch.from_numpy(x_np.reshape(-1)))
+        g.scales.fill_(-1.0)
+        g.codes.fill_(77)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        s_ref = oracle.compute_scales(x_np)
+        assert_bits_equal(g.scales.cpu().numpy().reshape(batch, D), s_ref, "scales after a replay")
+        assert_bits_equal(g.codes.cpu().numpy().reshape(batch, N, D), oracle.quantize(x_np, s_ref), "codes after a replay")
+        # the same call eagerly, on the default stream (its own workspace)
+        s_f, q_f = g.quantize_fused()
+        assert_bits_equal(s_f, s_ref, "scales, eager")
+        assert g.guards_intact()
 
 
 # ------------------------------------------------------------------ FP8 (E4M3) codes
