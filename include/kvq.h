@@ -23,7 +23,7 @@
  *    to KVQ_ERR_HIP.  Input and output buffers must not overlap.
  *  - the scale reductions (kvq_absmax_scales and its _t, _int4, _fp8 forms),
  *    kvq_roundtrip_error and kvq_attn_score_error keep a per-device, per-stream
- *    workspace (16 MiB of partial maxima and sums) that the library allocates with
+ *    workspace (16 MiB of partial maxima and sums, 4 KiB of counters) that the library allocates with
  *    hipMalloc on a stream's first such call (or in kvq_prepare_stream) and keeps
  *    until kvq_release_stream or the end of the process -- make that call outside
  *    any graph capture.  Two calls in flight on
@@ -218,13 +218,17 @@ kvq_status kvq_append_int4(const float *x_new, float *scales, float *scales_prev
                            kvq_stream_t stream);
 
 /*
- * Scale computation and quantization in one call (same results as
- * kvq_absmax_scales followed by kvq_quantize).  A slab of at most 65536
- * elements (D % 4 == 0, D <= 4096, 16-byte aligned x and scales) is held in
- * one workgroup's registers: one launch, x fetched from HBM once.  Larger
- * slabs run the two passes back to back.
+ * Scale computation and quantization in one call -- Eq. (scale_compute) and
+ * Eq. (quant_op); same results, bit for bit, as kvq_absmax_scales followed by
+ * kvq_quantize.  Slabs of at most 4096 rows (D % 4 == 0, 16-byte aligned x and
+ * scales, 4-byte aligned codes) are cut into column tiles that one workgroup
+ * holds on chip -- in registers up to 2048 rows, in registers and LDS up to
+ * 4096 (D <= 65536 there) -- so x is fetched from HBM once, in one launch.
+ * Taller slabs, other widths and other alignments run the two passes back to
+ * back.  The form for 2049 to 4096 rows keeps a few counters in the stream's
+ * workspace (see the notes at the top) and leaves them at zero.
  *   x [batch,N,D] fp32 read only; scales [batch,D] fp32 and codes [batch,N,D]
- *   int8 written.
+ *   int8 written.  Errors as for kvq_absmax_scales.
  */
 kvq_status kvq_quantize_fused(const float *x, float *scales, int8_t *codes,
                               int64_t batch, int64_t N, int64_t D, kvq_stream_t stream);

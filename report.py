@@ -70,20 +70,25 @@ def main():
     if args.fused and args.iters == 0:
         # for rocprofv3 --pmc: exactly one launch of each form, in this order, then a plain copy of known size
         kvq.kvq_prepare_stream()
-        saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES)
-        for (B, N, D, lanes) in [(256, 4096, 128, 4), (256, 2048, 256, 8), (512, 1024, 256, 8), (4096, 512, 128, 8)]:
+        saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
+        for (B, N, D, lanes, tall) in [(256, 4096, 128, 8, 1), (256, 4096, 128, 8, 2), (256, 4096, 128, 4, 0),
+                                       (2048, 4096, 128, 8, 1), (2048, 4096, 128, 8, 2), (256, 2048, 256, 8, 1),
+                                       (512, 1024, 256, 8, 1), (4096, 512, 128, 8, 1)]:
             E = B * N * D
             x = torch.randn(E, device="cuda")
             scales = torch.empty(B * D, device="cuda")
             codes = torch.empty(E, dtype=torch.int8, device="cuda")
             torch.cuda.synchronize()
             kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
+            kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)
             kvq.kvq_quantize_fused(x, scales, codes, B, N, D)
-            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved)
+            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved[0])
+            kvq.kvq_set_option(kvq.OPT_FUSED_TALL, saved[1])
             kvq.kvq_absmax_scales(x, scales, B, N, D)
             kvq.kvq_quantize(x, scales, codes, B, N, D)
             torch.cuda.synchronize()
-            print("launched: fused with tiles of >= %d lanes, then the two calls, on [%d x %d x %d]" % (lanes, B, N, D))
+            print("launched: fused with tiles of >= %d lanes, FUSED_TALL = %d, then the two calls, on [%d x %d x %d]"
+                  % (lanes, tall, B, N, D))
             del x, codes
             torch.cuda.empty_cache()
         a = torch.empty(1 << 27, device="cuda")
@@ -117,6 +122,33 @@ def main():
             torch.cuda.empty_cache()
         print()
         print("(in brackets: fraction of 8 TB/s at 5 B per element; a setting whose tiles do not fit falls back to the two calls)")
+        print()
+        print("Slabs of 2049 to 4096 rows (a 32-channel column tile in registers and LDS, persistent workgroups):")
+        print()
+        print("| batch x N x D | two calls ms | fused (default) ms | workgroups do not wait for their neighbours | register-only tiles of 16 channels |")
+        print("|---|---|---|---|---|")
+        saved_tall = kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
+        for (B, N, D) in [(256, 4096, 128), (512, 4096, 128), (2048, 4096, 128), (64, 4096, 512), (256, 3072, 128),
+                          (1024, 2304, 256)]:
+            E = B * N * D
+            x = torch.randn(E, device="cuda")
+            scales = torch.empty(B * D, device="cuda")
+            codes = torch.empty(E, dtype=torch.int8, device="cuda")
+            two, _ = timeit(lambda: (kvq.kvq_absmax_scales(x, scales, B, N, D), kvq.kvq_quantize(x, scales, codes, B, N, D)))
+            cells = []
+            for tall, lanes in ((saved_tall, saved[0]), (2, saved[0]), (0, 4)):
+                kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)
+                kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
+                kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, 16 if tall == 0 else saved[1])
+                t, _ = timeit(lambda: kvq.kvq_quantize_fused(x, scales, codes, B, N, D))
+                cells.append("%.4f (%.3f)" % (t, 5.0 * E / t / 1e6 / 8000.0))
+            kvq.kvq_set_option(kvq.OPT_FUSED_TALL, saved_tall)
+            kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved[0])
+            kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, saved[1])
+            print("| %d x %d x %d | %.4f | %s |" % (B, N, D, two, " | ".join(cells)))
+            sys.stdout.flush()
+            del x, codes
+            torch.cuda.empty_cache()
         if args.calibration_copy:
             a = torch.empty(1 << 27, device="cuda")
             b = torch.empty(1 << 27, device="cuda")
