@@ -324,9 +324,10 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
                               int64_t D, kvq_stream_t stream) {
   if (!x || !scales || !codes) return KVQ_ERR_NULL;
   if (kvq_status s = check_shape(batch, N, D)) return s;
-  // A slab that fits one workgroup's registers is read once; anything larger needs every row of a
-  // column before its first code can be written, i.e. two passes over x.  (Splitting the batch into
-  // groups small enough for the 256 MiB memory-side cache was measured and gave no reuse.)
+  // A slab whose column tiles fit one workgroup's registers (up to 2048 rows), or the registers and LDS of a
+  // compute unit (up to 4096), is read once; anything taller needs every row of a column before its first
+  // code can be written, i.e. two passes over x.  (Splitting the batch into groups small enough for the
+  // 256 MiB memory-side cache was measured and gave no reuse.)
   if (fused_slab_applicable(x, scales, codes, N, D)) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
   if (fused_tall_applicable(x, scales, codes, N, D)) {
     Workspace ws;

@@ -11,7 +11,8 @@
 // x, 32-byte segments of codes), which reaches N = 2048; narrower tiles are possible down to 16
 // channels (N = 4096) but do not beat two passes (see fused_tile_tx_log2).  Neighbouring tiles share
 // cache lines, so the tiles of a slab are numbered such that they run on the same XCD one after the
-// other and meet in its L2.  Taller slabs take the two-pass path.
+// other and meet in its L2.  Slabs of 2049 to 4096 rows have a kernel of their own (kvq_fused_tall.hip);
+// taller ones take the two-pass path.
 #include <type_traits>
 
 #include "kvq_internal.h"
