@@ -63,6 +63,27 @@ def test_random_shapes_offsets_and_entry_points(seed):
             assert g.guards_intact(), tag
 
 
+@pytest.mark.parametrize("seed", [30, 31])
+def test_random_shapes_fused_call_on_tall_slabs(seed):
+    """kvq_quantize_fused on slabs of 2049 to 4096 rows: any width that is a multiple of 4, few and many
+    slabs (one tile or several per workgroup), buffers at and off 16-byte alignment (off it: two passes)."""
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        N = int(rng.integers(2049, 4097))
+        D = int(rng.choice([4, 8, 20, 32, 36, 64, 100, 128, 132, 256, 260, 516]))
+        batch = int(rng.integers(1, max(2, min(90, 9000000 // (N * D)))))
+        off = int(rng.choice([0, 0, 4, 8, 1, 2]))
+        tag = "seed %d case %d: shape (%d,%d,%d) offset %d" % (seed, case, batch, N, D, off)
+        print(tag, flush=True)
+        x = T.make_matrix(rng, batch, N, D)
+        g = T.Gpu(x, offset=off)
+        s_ref = oracle.compute_scales(x)
+        sc, cd = g.quantize_fused()
+        T.assert_bits_equal(sc, s_ref, tag + " fused scales")
+        T.assert_bits_equal(cd, oracle.quantize(x, s_ref), tag + " fused codes")
+        assert g.guards_intact(), tag
+
+
 @pytest.mark.parametrize("seed", [10, 11])
 def test_random_shapes_sixteen_bit_inputs_and_wide_rows(seed):
     """fp16 / bf16 matrices and appended tokens, and fp32 round trips on rows wide enough for the
