@@ -14,6 +14,10 @@
 // All loads and stores go through buffer descriptors sized to the tile, so rows past N, channels past D
 // and the tile after a workgroup's last one need no branches: loads beyond the descriptor return zero
 // (which leaves a maximum of absolute values alone) and stores beyond it are dropped.
+//
+// A tile's rows of codes are 32 bytes, a quarter of a cache line; the other quarters are written by the
+// workgroups that hold the neighbouring tiles.  Those run on the same XCD in the same turn and, before each
+// tile, wait for each other for a bounded time (a hint for speed only), so that the quarters meet in L2.
 #include <atomic>
 #include <type_traits>
 #include <utility>
