@@ -325,15 +325,16 @@ kvq_status kvq_quantize_fused(const float* x, float* scales, int8_t* codes, int6
   if (!x || !scales || !codes) return KVQ_ERR_NULL;
   if (kvq_status s = check_shape(batch, N, D)) return s;
   // A slab whose column tiles fit one workgroup's registers (up to 2048 rows), or the registers and LDS of a
-  // compute unit (up to 4096), is read once; anything taller needs every row of a column before its first
-  // code can be written, i.e. two passes over x.  (Splitting the batch into groups small enough for the
+  // compute unit (up to 4096; also the faster form for many shorter slabs), is read once; anything taller
+  // needs every row of a column before its first code can be written, i.e. two passes over x.  (Splitting the batch into groups small enough for the
   // 256 MiB memory-side cache was measured and gave no reuse.)
-  if (fused_slab_applicable(x, scales, codes, N, D)) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
-  if (fused_tall_applicable(x, scales, codes, N, D)) {
+  const bool slab_form = fused_slab_applicable(x, scales, codes, N, D);
+  if (fused_tall_applicable(x, scales, codes, batch, N, D, slab_form)) {
     Workspace ws;
     if (kvq_status s = get_workspace(stream, &ws)) return s;
     return launch_fused_tall(x, scales, codes, batch, N, D, ws, stream);
   }
+  if (slab_form) return launch_fused_slab(x, scales, codes, batch, N, D, stream);
   if (kvq_status s = launch_absmax_scales(x, scales, batch, N, D, stream)) return s;
   return launch_quantize(x, scales, codes, batch, N, D, stream);
 }

@@ -198,7 +198,7 @@ kvq_status kvq_set_option(int key, int value) {
       o.attn_form = value;
       return KVQ_OK;
     case KVQ_OPT_FUSED_TALL:
-      if (value < 0 || value > 2) return KVQ_ERR_ARG;
+      if (value < 0 || value > 3) return KVQ_ERR_ARG;
       o.fused_tall = value;
       return KVQ_OK;
     default:

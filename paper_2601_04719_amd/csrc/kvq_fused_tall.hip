@@ -28,17 +28,17 @@ namespace kvq {
 
 namespace {
 
-constexpr int kTallBlock = 512;   // lanes: 8 along a row (32 channels) x 64 down the rows
-constexpr int kTallTX = 8, kTallTY = kTallBlock / kTallTX;
+constexpr int kTallBlock = 512;   // lanes: TX along a row (4 TX channels) x 512 / TX down the rows
 constexpr int kTallRegRows = 46;  // rows per lane held in registers
 constexpr int kTallLdsRows = 18;  // rows per lane held in LDS
 constexpr int kTallBatches = 6;   // a tile's rows are worked through in this many batches
 constexpr int kTallStage = (kTallLdsRows + kTallBatches - 1) / kTallBatches;  // rows staged on their way to LDS
-constexpr int kTallRows = kTallTY * (kTallRegRows + kTallLdsRows);  // 4096
+constexpr int kTallRowsPerLane = kTallRegRows + kTallLdsRows;  // 64: a tile is up to 64 * 512 / TX rows tall
 constexpr int kTallWaves = kTallBlock / 64;
-constexpr size_t kTallLdsBytes =
-    (size_t)kTallLdsRows * kTallBlock * 16 + 2 * (size_t)kTallWaves * kTallTX * 16;
-static_assert(kTallLdsBytes <= 160 * 1024, "LDS of one compute unit");
+constexpr size_t tall_lds_bytes(int tx) {
+  return (size_t)kTallLdsRows * kTallBlock * 16 + 2 * (size_t)kTallWaves * tx * 16;
+}
+static_assert(tall_lds_bytes(64) <= 160 * 1024, "LDS of one compute unit");
 constexpr int kTallXcds = 8;              // workgroup i of a launch is handed to XCD i % 8
 constexpr int kTallPolls = 64;             // how often a workgroup looks for its neighbours before it goes on alone
 constexpr uint32_t kOutside = 0x80000000u;  // an offset no descriptor reaches, whatever is added below 2^31
@@ -72,6 +72,9 @@ struct TallTile {
   uint32_t quad_in_slab;  // quad % quads_per_slab
 };
 
+// TXLOG: log2 of the lanes along a row (8 to 64: tiles of 32 to 256 channels, up to 4096 down to 512 rows).
+// NT: streaming stores, for tiles whose rows of codes are whole cache lines.
+template <int TXLOG, bool NT>
 __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* __restrict__ x,
                                                                    float* __restrict__ scales,
                                                                    int8_t* __restrict__ codes, uint32_t total_quads,
@@ -79,6 +82,8 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
                                                                    uint32_t step_slabs, uint32_t step_quads,
                                                                    uint32_t N, uint32_t D,
                                                                    uint32_t* __restrict__ tickets) {
+  constexpr int kTallTX = 1 << TXLOG, kTallTY = kTallBlock / kTallTX;
+  static_assert(kTallTX >= 8 && kTallTX <= 64, "a wavefront holds every column group of the tile");
   extern __shared__ __align__(16) unsigned char tall_lds[];
   f32x4* const rows = reinterpret_cast<f32x4*>(tall_lds);       // [kTallLdsRows][kTallBlock], slot per lane
   f32x4* const red = rows + kTallLdsRows * kTallBlock;          // [2][kTallWaves][kTallTX]
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
       return __builtin_bit_cast(f32x4, w);
     };
     auto put = [&](const f32x4& r, int row) {
-      __builtin_amdgcn_raw_buffer_store_b32(encode(r), cx, (int)(co + (uint32_t)row * cstep), 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(encode(r), cx, (int)(co + (uint32_t)row * cstep), 0, NT ? 2 : 0);
     };
     f32x4 staged[kTallStage];
 #pragma unroll
@@ -223,12 +228,11 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
       nxt.slab += 1;
     }
 
-    // column maxima: over the 8 lanes of a wavefront that share a column group, then over the wavefronts
+    // column maxima: over the lanes of a wavefront that share a column group, then over the wavefronts
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      m[i] = fmaxf(m[i], __shfl_xor(m[i], 8));
-      m[i] = fmaxf(m[i], __shfl_xor(m[i], 16));
-      m[i] = fmaxf(m[i], __shfl_xor(m[i], 32));
+#pragma unroll
+      for (int s = kTallTX; s < 64; s <<= 1) m[i] = fmaxf(m[i], __shfl_xor(m[i], s));
     }
     f32x4* const slot = red + parity * (kTallWaves * kTallTX);
     if (lane < kTallTX) slot[wave * kTallTX + lane] = f32x4{m[0], m[1], m[2], m[3]};
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
 
 }  // namespace
 
-// The kernel asks for more dynamic LDS than a kernel gets by default: raise its limit, once per device
+// The kernels ask for more dynamic LDS than a kernel gets by default: raise their limits, once per device
 // (also from kvq_prepare_stream, so that nothing but launches is left for a stream capture).
 kvq_status prepare_fused_tall() {
   static std::atomic<uint64_t> done{0};
@@ -279,18 +283,52 @@ kvq_status prepare_fused_tall() {
   KVQ_HIP(hipGetDevice(&dev));
   const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
   if (bit && (done.load(std::memory_order_acquire) & bit)) return KVQ_OK;
-  KVQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tall_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTallLdsBytes));
+#define KVQ_RAISE_LDS(TXLOG_, NT_)                                                                    \
+  KVQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tall_kernel<TXLOG_, NT_>),         \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tall_lds_bytes(1 << TXLOG_)))
+  KVQ_RAISE_LDS(3, false);
+  KVQ_RAISE_LDS(4, false);
+  KVQ_RAISE_LDS(5, false);
+  KVQ_RAISE_LDS(5, true);
+  KVQ_RAISE_LDS(6, false);
+  KVQ_RAISE_LDS(6, true);
+#undef KVQ_RAISE_LDS
   if (bit) done.fetch_or(bit, std::memory_order_release);
   return KVQ_OK;
 }
 
-// Slabs taller than the register-only kernel reaches with 32-channel tiles, up to 4096 rows; every byte
-// offset inside a tile (up to 4096 rows of D floats, plus the marker for lanes outside) within 32 bits.
-bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D) {
-  if (options().fused_tall == 0) return false;
+// log2 of the lanes along a row: the widest tile (up to 256 channels, no wider than the rows) whose
+// 64 rows per lane still reach N
+static int tall_tx_log2(int64_t N, int64_t D) {
+  int l = 3;
+  while (l < 6 && N <= (int64_t)kTallRowsPerLane * (kTallBlock >> (l + 1)) && ((int64_t)4 << l) < D) l++;
+  return l;
+}
+
+// Whether kvq_quantize_fused gives a problem to these kernels; `slab_form` says that the register-only kernel
+// (kvq_fused.hip) could take it too.  The tile has to be more than half full (the arithmetic of a turn is
+// that of a full tile), every byte offset inside it has to fit 32 bits, and then, measured
+// (profiles/fused_column_tiles.md):
+//  - more than 1024 rows (tiles of 32 or 64 channels): always -- [256 x 2048 x 256] 0.138 against 0.178 ms
+//    for the register-only kernel, whose 16 rows per lane leave one workgroup per compute unit with nothing
+//    to overlap;
+//  - up to 1024 rows (tiles of 128 or 256 channels): only without the other kernel, or with whole tiles and
+//    at least eight of them per compute unit -- [2048 x 1024 x 128] 0.243 against 0.262 ms, but
+//    [512 x 1024 x 256] (four tiles per unit: the first and the last turn of a workgroup are half idle)
+//    0.144 against 0.138 ms, and a last tile of a few channels costs a whole turn.
+// KVQ_OPT_FUSED_TALL = 3 takes every problem whose tiles are more than half full.
+bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t batch, int64_t N,
+                           int64_t D, bool slab_form) {
+  const int mode = options().fused_tall;
+  if (mode == 0) return false;
   if (D % 4 || !aligned(x, 16) || !aligned(scales, 16) || !aligned(codes, 4)) return false;
-  return N > kTallRows / 2 && N <= kTallRows && D <= 65536;
+  if (N > kTallRowsPerLane * (kTallBlock >> 3) || D > 65536) return false;
+  const int tx_log2 = tall_tx_log2(N, D);
+  if (2 * N <= (int64_t)kTallRowsPerLane * (kTallBlock >> tx_log2)) return false;
+  if (mode == 3 || tx_log2 <= 4 || !slab_form) return true;
+  const int64_t tile_channels = (int64_t)4 << tx_log2;
+  const DeviceInfo dev = current_device();
+  return D % tile_channels == 0 && batch * (D / tile_channels) >= 8 * (int64_t)dev.cus;
 }
 
 kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
@@ -298,8 +336,13 @@ kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64
   const DeviceInfo dev = current_device();
   if (dev.cus <= 0) return hip_failed(hipErrorInvalidDevice);
   if (kvq_status s = prepare_fused_tall()) return s;
-  const int64_t ctiles = (D + kTallTX * 4 - 1) / (kTallTX * 4);
-  const int quad_log2 = ctiles < 2 ? 0 : ctiles < 3 ? 1 : 2;  // four column tiles share a 128-byte line of codes
+  const int tx_log2 = tall_tx_log2(N, D);
+  const int64_t tile_channels = (int64_t)4 << tx_log2;
+  const int64_t ctiles = (D + tile_channels - 1) / tile_channels;
+  // column tiles that share a 128-byte line of codes: four of 32 channels, two of 64, else each has its own
+  const int line_log2 = tx_log2 == 3 ? 2 : tx_log2 == 4 ? 1 : 0;
+  int quad_log2 = 0;
+  while (quad_log2 < line_log2 && ((int64_t)1 << quad_log2) < ctiles) quad_log2++;
   const int64_t quad_tiles = (int64_t)1 << quad_log2;
   const int64_t quads_per_slab = (ctiles + quad_tiles - 1) / quad_tiles;
   if (batch > INT32_MAX / (2 * kTallXcds) / quads_per_slab) return KVQ_ERR_OVERFLOW;
@@ -313,11 +356,22 @@ kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64
   const int64_t step = kTallXcds * (per_xcd / quad_tiles);  // in quads, slab-major
   // a counter per group of neighbours; none where a quad is a single tile or the workspace has too few
   uint32_t* const tickets =
-      options().fused_tall == 1 && quad_tiles > 1 && step <= kTickets ? ws.tickets : nullptr;
-  hipLaunchKernelGGL(fused_tall_kernel, dim3((uint32_t)(per_xcd * kTallXcds)), dim3(kTallBlock), kTallLdsBytes,
-                     stream, x, scales, codes, (uint32_t)total_quads, (uint32_t)quads_per_slab, (uint32_t)quad_log2,
-                     (uint32_t)(step / quads_per_slab), (uint32_t)(step % quads_per_slab), (uint32_t)N,
-                     (uint32_t)D, tickets);
+      options().fused_tall != 2 && quad_tiles > 1 && step <= kTickets ? ws.tickets : nullptr;
+  // rows of codes that are whole cache lines can be streamed out
+  const bool nt = tx_log2 >= 5 && D % 128 == 0 && aligned(codes, 128);
+  const dim3 grid((uint32_t)(per_xcd * kTallXcds)), block(kTallBlock);
+#define KVQ_LAUNCH_TALL(TXLOG_, NT_)                                                                              \
+  hipLaunchKernelGGL((fused_tall_kernel<TXLOG_, NT_>), grid, block, tall_lds_bytes(1 << TXLOG_), stream, x, scales, \
+                     codes, (uint32_t)total_quads, (uint32_t)quads_per_slab, (uint32_t)quad_log2,                 \
+                     (uint32_t)(step / quads_per_slab), (uint32_t)(step % quads_per_slab), (uint32_t)N,           \
+                     (uint32_t)D, tickets)
+  if (tx_log2 == 3) KVQ_LAUNCH_TALL(3, false);
+  else if (tx_log2 == 4) KVQ_LAUNCH_TALL(4, false);
+  else if (tx_log2 == 5 && nt) KVQ_LAUNCH_TALL(5, true);
+  else if (tx_log2 == 5) KVQ_LAUNCH_TALL(5, false);
+  else if (nt) KVQ_LAUNCH_TALL(6, true);
+  else KVQ_LAUNCH_TALL(6, false);
+#undef KVQ_LAUNCH_TALL
   KVQ_HIP(hipGetLastError());
   return KVQ_OK;
 }

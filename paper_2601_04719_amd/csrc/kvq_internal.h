@@ -79,7 +79,7 @@ struct Options {
   int append_blocks_per_cu = 32;  // row chunking of the requantization pass of kvq_append
   int fused_min_lanes = 8;        // narrowest column tile of the single-pass fused kernel, in 16-byte lanes along a row
   int fused_max_rows = 0;         // rows a lane of that kernel holds: 4, 8, 16, or 0 = 8 where the tiles stay wide enough, else 16
-  int fused_tall = 1;             // slabs of 2049..4096 rows: 1 = the single-pass kernel that also keeps rows in LDS, 0 = two passes, 2 = as 1 but workgroups do not wait for their neighbours
+  int fused_tall = 1;             // the persistent single-pass kernel that also keeps rows in LDS: 1 = where it is the faster form, 0 = never, 2 = as 1 but workgroups do not wait for their neighbours, 3 = wherever its tiles are more than half full
   int attn_form = 0;              // score-error contraction: 0 = bf16 pieces where the shape allows, 1 = fp32 matrix cores always
 };
 Options& options();
@@ -173,7 +173,8 @@ kvq_status launch_dequantize(const int8_t* codes, const float* scales, float* x_
                              int64_t N, int64_t D, hipStream_t stream);
 // One-pass absmax + quantize for slabs that fit one workgroup's registers.
 bool fused_slab_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D);
-bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t N, int64_t D);
+bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t batch, int64_t N,
+                           int64_t D, bool slab_form);
 kvq_status prepare_fused_tall();
 kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,
                              const Workspace& ws, hipStream_t stream);

@@ -101,7 +101,7 @@ def test_options_round_trip_and_reject_bad_values():
                            (kvq.OPT_ABSMAX_UNROLL, 4, 5), (kvq.OPT_ABSMAX_PASSES, 2, -1),
                            (kvq.OPT_ABSMAX_SPAN, 2, 3), (kvq.OPT_ABSMAX_BLOCKS_PER_CU, 4, 0),
                            (kvq.OPT_APPEND_BLOCKS_PER_CU, 32, 0), (kvq.OPT_FUSED_MIN_LANES, 4, 12),
-                           (kvq.OPT_FUSED_MAX_ROWS, 4, 5), (kvq.OPT_ATTN_FORM, 1, 2), (kvq.OPT_FUSED_TALL, 0, 3)]:
+                           (kvq.OPT_FUSED_MAX_ROWS, 4, 5), (kvq.OPT_ATTN_FORM, 1, 2), (kvq.OPT_FUSED_TALL, 0, 4)]:
         old = kvq.kvq_get_option(key)
         kvq.kvq_set_option(key, good)
         assert kvq.kvq_get_option(key) == good

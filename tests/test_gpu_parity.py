@@ -629,7 +629,9 @@ FUSED_SHAPES = [(7, 512, 128), (3, 1000, 64), (2, 16, 4096), (5, 17, 20), (1, 16
                 (17, 4095, 20), (8, 1025, 136), (1, 4097, 128), (2, 700, 4100),
                 # 2049 to 4096 rows: a 32-channel column tile in the registers and LDS of a persistent workgroup;
                 # more tiles than workgroups, quads of tiles with empty places, one row past the register-only form
-                (70, 4096, 128), (33, 3100, 260), (1, 2049, 128), (2, 4096, 36), (5, 2500, 1000), (600, 2050, 8)]
+                (70, 4096, 128), (33, 3100, 260), (1, 2049, 128), (2, 4096, 36), (5, 2500, 1000), (600, 2050, 8),
+                # the same with tiles of 64, 128 and 256 channels (1025 to 2048, 513 to 1024, 257 to 512 rows)
+                (140, 2000, 128), (300, 1024, 128), (150, 512, 512), (7, 1900, 72), (3, 600, 1028), (2, 300, 2048)]
 
 
 @pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -642,10 +644,10 @@ def test_single_pass_fused_slabs(shape):
     saved = (kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS),
              kvq.kvq_get_option(kvq.OPT_FUSED_TALL))
     try:
-        # the defaults; the narrowest column tiles with every register depth; wide tiles only; the form for
-        # 2049 to 4096 rows without its workgroups waiting for each other; and without that form (two passes)
+        # the defaults; the narrowest column tiles with every register depth; wide tiles only; the persistent
+        # form without its workgroups waiting for each other, wherever its tiles are at least half full, never
         for min_lanes, max_rows, tall in (saved, (4, 16, 1), (4, 8, 1), (4, 4, 1), (64, 0, 1), (saved[0], saved[1], 2),
-                                         (saved[0], saved[1], 0)):
+                                         (saved[0], saved[1], 3), (saved[0], saved[1], 0)):
             kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, min_lanes)
             kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, max_rows)
             kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)

@@ -65,23 +65,31 @@ def test_random_shapes_offsets_and_entry_points(seed):
 
 @pytest.mark.parametrize("seed", [30, 31])
 def test_random_shapes_fused_call_on_tall_slabs(seed):
-    """kvq_quantize_fused on slabs of 2049 to 4096 rows: any width that is a multiple of 4, few and many
-    slabs (one tile or several per workgroup), buffers at and off 16-byte alignment (off it: two passes)."""
+    """kvq_quantize_fused on slabs of 257 to 4096 rows, by the default choice of kernel and with the persistent
+    one wherever its tiles are at least half full: any width that is a multiple of 4, few and many slabs
+    (one tile or several per workgroup), buffers at and off 16-byte alignment (off it: two passes)."""
+    from paper_2601_04719_amd import kvq
     rng = np.random.default_rng(seed)
-    for case in range(14):
-        N = int(rng.integers(2049, 4097))
-        D = int(rng.choice([4, 8, 20, 32, 36, 64, 100, 128, 132, 256, 260, 516]))
-        batch = int(rng.integers(1, max(2, min(90, 9000000 // (N * D)))))
-        off = int(rng.choice([0, 0, 4, 8, 1, 2]))
-        tag = "seed %d case %d: shape (%d,%d,%d) offset %d" % (seed, case, batch, N, D, off)
-        print(tag, flush=True)
-        x = T.make_matrix(rng, batch, N, D)
-        g = T.Gpu(x, offset=off)
-        s_ref = oracle.compute_scales(x)
-        sc, cd = g.quantize_fused()
-        T.assert_bits_equal(sc, s_ref, tag + " fused scales")
-        T.assert_bits_equal(cd, oracle.quantize(x, s_ref), tag + " fused codes")
-        assert g.guards_intact(), tag
+    saved = kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
+    try:
+        for case in range(24):
+            N = int(rng.integers(2049, 4097)) if case % 3 == 0 else int(rng.integers(257, 2049))
+            D = int(rng.choice([4, 8, 20, 32, 36, 64, 100, 128, 132, 256, 260, 516, 1024]))
+            batch = int(rng.integers(1, max(2, min(400, 9000000 // (N * D)))))
+            off = int(rng.choice([0, 0, 4, 8, 1, 2]))
+            mode = 3 if case % 2 else 1
+            tag = "seed %d case %d: shape (%d,%d,%d) offset %d mode %d" % (seed, case, batch, N, D, off, mode)
+            print(tag, flush=True)
+            kvq.kvq_set_option(kvq.OPT_FUSED_TALL, mode)
+            x = T.make_matrix(rng, batch, N, D)
+            g = T.Gpu(x, offset=off)
+            s_ref = oracle.compute_scales(x)
+            sc, cd = g.quantize_fused()
+            T.assert_bits_equal(sc, s_ref, tag + " fused scales")
+            T.assert_bits_equal(cd, oracle.quantize(x, s_ref), tag + " fused codes")
+            assert g.guards_intact(), tag
+    finally:
+        kvq.kvq_set_option(kvq.OPT_FUSED_TALL, saved)
 
 
 @pytest.mark.parametrize("seed", [10, 11])
