@@ -225,7 +225,7 @@ kvq_status kvq_append_int4(const float *x_new, float *scales, float *scales_prev
  * holds on chip -- in registers up to 2048 rows, in registers and LDS up to
  * 4096 (D <= 65536 there) -- so x is fetched from HBM once, in one launch.
  * Taller slabs, other widths and other alignments run the two passes back to
- * back.  The form for 2049 to 4096 rows keeps a few counters in the stream's
+ * back.  The form that also uses LDS keeps a few counters in the stream's
  * workspace (see the notes at the top) and leaves them at zero.
  *   x [batch,N,D] fp32 read only; scales [batch,D] fp32 and codes [batch,N,D]
  *   int8 written.  Errors as for kvq_absmax_scales.

@@ -87,9 +87,11 @@ kvq_status kvq_probe_clock(uint64_t *ticks_out, int microseconds, kvq_stream_t s
  *                           tiles take the two-pass path
  *   KVQ_OPT_FUSED_MAX_ROWS  rows of its tile a lane of that kernel holds in registers: 4, 8 or 16;
  *                           0 = 8 where the tiles stay at least FUSED_MIN_LANES wide, else 16
- *   KVQ_OPT_FUSED_TALL      slabs of 2049 to 4096 rows in kvq_quantize_fused: 1 (default) = the single-pass kernel
- *                           that holds a 32-channel column tile in registers and LDS, 0 = two passes, 2 = as 1
- *                           but its workgroups do not wait for the neighbours they share lines of codes with
+ *   KVQ_OPT_FUSED_TALL      the persistent single-pass kernel of kvq_quantize_fused (a column tile of 32 to 256
+ *                           channels in the registers and LDS of one workgroup per compute unit; slabs of up to
+ *                           4096 rows): 1 (default) = where it is the faster form, 0 = never, 2 = as 1 but its
+ *                           workgroups do not wait for the neighbours they share lines of codes with, 3 = wherever
+ *                           its tiles are more than half full
  *   KVQ_OPT_ATTN_FORM       which matrix cores kvq_attn_score_error contracts on: 0 = bf16 (every operand as
  *                           three bf16 pieces) where the shape allows, else fp32; 1 = fp32 always.  The two
  *                           forms round differently (both within the bound stated in kvq.h)

@@ -1,5 +1,5 @@
-// Scale computation and quantization in one pass for slabs of 2049 to 4096 rows
-// (paper: Eq. (scale_compute) + Eq. (quant_op); same results as the two separate kernels).
+// Scale computation and quantization in one pass, with the column tile in the registers and LDS of a
+// persistent workgroup (paper: Eq. (scale_compute) + Eq. (quant_op); same results as the two separate kernels).
 //
 // The single pass has to hold all N rows of the columns it works on.  Up to N = 2048 a column tile of
 // 32 channels (one 128-byte line of x per row) fits the registers of a workgroup (kvq_fused.hip).  At
@@ -8,16 +8,19 @@
 // in a private slot of LDS (144 KiB in all).  With a single workgroup per unit nothing else hides the
 // phases of a tile behind each other, so the workgroup is persistent and pipelines them itself: while it
 // quantizes and stores the rows of one tile, register by register, it issues the loads of the next tile
-// into the registers just freed.  Only the reduction of the column maxima (three lane exchanges, one
-// barrier) runs with nothing in flight.
+// into the registers just freed.  Only the reduction of the column maxima (lane exchanges, one barrier)
+// runs with nothing in flight.  The same 64 rows per lane make tiles of 64 channels x 2048 rows, 128 x 1024
+// and 256 x 512; which problems take this kernel and which the register-only one is decided, from
+// measurements, in fused_tall_applicable.
 //
 // All loads and stores go through buffer descriptors sized to the tile, so rows past N, channels past D
 // and the tile after a workgroup's last one need no branches: loads beyond the descriptor return zero
 // (which leaves a maximum of absolute values alone) and stores beyond it are dropped.
 //
-// A tile's rows of codes are 32 bytes, a quarter of a cache line; the other quarters are written by the
-// workgroups that hold the neighbouring tiles.  Those run on the same XCD in the same turn and, before each
-// tile, wait for each other for a bounded time (a hint for speed only), so that the quarters meet in L2.
+// A 32-channel tile's rows of codes are 32 bytes, a quarter of a cache line (64 channels: half); the other
+// pieces are written by the workgroups that hold the neighbouring tiles.  Those run on the same XCD in the
+// same turn and, before each tile, wait for each other for a bounded time (a hint for speed only), so that
+// the pieces meet in L2.  Wider tiles write whole lines and stream them out.
 #include <atomic>
 #include <type_traits>
 #include <utility>

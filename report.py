@@ -72,7 +72,7 @@ def main():
         kvq.kvq_prepare_stream()
         saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
         for (B, N, D, lanes, tall) in [(256, 4096, 128, 8, 1), (256, 4096, 128, 8, 2), (256, 4096, 128, 4, 0),
-                                       (2048, 4096, 128, 8, 1), (2048, 4096, 128, 8, 2), (256, 2048, 256, 8, 1),
+                                       (2048, 4096, 128, 8, 1), (2048, 4096, 128, 8, 2), (256, 2048, 256, 8, 1), (256, 2048, 256, 8, 0),
                                        (512, 1024, 256, 8, 1), (4096, 512, 128, 8, 1)]:
             E = B * N * D
             x = torch.randn(E, device="cuda")
@@ -98,6 +98,8 @@ def main():
         return
 
     if args.fused:
+        print("The register-only kernel by rows per lane and narrowest tile (fused_slab_kernel; the persistent kernel switched off except in the default column):")
+        print()
         print("| batch x N x D | two calls ms | fused (default) ms | 16 rows/lane, tiles >= 8 lanes | 16 rows, >= 4 lanes | 8 rows, >= 8 lanes | 8 rows, >= 4 lanes | 4 rows, >= 4 lanes |")
         print("|---|---|---|---|---|---|---|---|")
         saved = kvq.kvq_get_option(kvq.OPT_FUSED_MIN_LANES), kvq.kvq_get_option(kvq.OPT_FUSED_MAX_ROWS)
@@ -109,13 +111,16 @@ def main():
             codes = torch.empty(E, dtype=torch.int8, device="cuda")
             two, _ = timeit(lambda: (kvq.kvq_absmax_scales(x, scales, B, N, D), kvq.kvq_quantize(x, scales, codes, B, N, D)))
             cells = []
-            for lanes, rows in (saved, (8, 16), (4, 16), (8, 8), (4, 8), (4, 4)):
+            tall0 = kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
+            for i, (lanes, rows) in enumerate((saved, (8, 16), (4, 16), (8, 8), (4, 8), (4, 4))):
                 kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
                 kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, rows)
+                kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall0 if i == 0 else 0)  # the other columns: this kernel's forms only
                 t, _ = timeit(lambda: kvq.kvq_quantize_fused(x, scales, codes, B, N, D))
                 cells.append("%.4f (%.3f)" % (t, 5.0 * E / t / 1e6 / 8000.0))
             kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, saved[0])
             kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, saved[1])
+            kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall0)
             print("| %d x %d x %d | %.4f | %s |" % (B, N, D, two, " | ".join(cells)))
             sys.stdout.flush()
             del x, codes
@@ -123,23 +128,24 @@ def main():
         print()
         print("(in brackets: fraction of 8 TB/s at 5 B per element; a setting whose tiles do not fit falls back to the two calls)")
         print()
-        print("Slabs of 2049 to 4096 rows (a 32-channel column tile in registers and LDS, persistent workgroups):")
+        print("The persistent kernel (a column tile of 32 to 256 channels in the registers and LDS of one workgroup per compute unit):")
         print()
-        print("| batch x N x D | two calls ms | fused (default) ms | workgroups do not wait for their neighbours | register-only tiles of 16 channels |")
-        print("|---|---|---|---|---|")
+        print("| batch x N x D | two calls ms | fused (default) ms | its workgroups do not wait for their neighbours | wherever its tiles are at least half full | never (register-only kernel, tiles down to 16 channels) |")
+        print("|---|---|---|---|---|---|")
         saved_tall = kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
         for (B, N, D) in [(256, 4096, 128), (512, 4096, 128), (2048, 4096, 128), (64, 4096, 512), (256, 3072, 128),
-                          (1024, 2304, 256)]:
+                          (1024, 2304, 256), (256, 2048, 256), (512, 2048, 128), (2048, 2048, 128), (512, 1024, 256),
+                          (2048, 1024, 128), (512, 512, 1024)]:
             E = B * N * D
             x = torch.randn(E, device="cuda")
             scales = torch.empty(B * D, device="cuda")
             codes = torch.empty(E, dtype=torch.int8, device="cuda")
             two, _ = timeit(lambda: (kvq.kvq_absmax_scales(x, scales, B, N, D), kvq.kvq_quantize(x, scales, codes, B, N, D)))
             cells = []
-            for tall, lanes in ((saved_tall, saved[0]), (2, saved[0]), (0, 4)):
+            for tall, lanes in ((saved_tall, saved[0]), (2, saved[0]), (3, saved[0]), (0, 4)):
                 kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)
                 kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
-                kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, 16 if tall == 0 else saved[1])
+                kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, 16 if (tall == 0 and N > 2048) else saved[1])
                 t, _ = timeit(lambda: kvq.kvq_quantize_fused(x, scales, codes, B, N, D))
                 cells.append("%.4f (%.3f)" % (t, 5.0 * E / t / 1e6 / 8000.0))
             kvq.kvq_set_option(kvq.OPT_FUSED_TALL, saved_tall)
