@@ -208,6 +208,10 @@ def time_extras(kvq, torch, timer, h, x, x_hat, codes, scales, E, N, D):
     out["append_int4_one_token_no_growth"] = row(lambda: kvq.kvq_append_int4(tok4, s3, prev, p4, B // 2, 4095, 1, 4096,
                                                                              128, stream=h),
                                                  cache="[%d x 4096 x 128] 4-bit" % (B // 2))
+    # scales and codes in one pass over x, on the decode-like view (a 32-channel column tile of a slab on chip)
+    sf = torch.empty(B * 128, device=x.device)
+    out["quantize_fused[%dx4096x128]" % B] = row(lambda: kvq.kvq_quantize_fused(x, sf, codes, B, 4096, 128, stream=h),
+                                                 5.0 * E + 4.0 * B * 128, note="two calls move 9 B per element")
     # the workload as a bf16 matrix (2 B in, 1 B out per element)
     x16 = x.to(torch.bfloat16)
     kvq.kvq_absmax_scales_t(kvq.DTYPE_BF16, x16, scales, 1, N, D, stream=h)
