@@ -7,7 +7,7 @@ on the 1B-element stress configuration (fp32 [131072 x 8192], Student-t(3) entri
 log-uniform per-channel spread, 1 % of channels all zero).  Inputs are generated on the host from a
 fixed seed and copied to HBM before the timed region.
 
-Prints one JSON line.  `value` is the metric BASELINE.json names, "quant+dequant GB/s": the
+Prints one JSON line.  `value` is the headline metric of this workload, "quant+dequant GB/s": the
 algorithmic bytes of quantize (4 B read + 1 B written per element) plus dequantize (1 B + 4 B)
 divided by the summed mean durations of those two calls inside the timed steps, measured with HIP
 events on the launch stream.  Every call's own time, GB/s and fraction of the 8 TB/s HBM peak are
