@@ -75,11 +75,11 @@ __global__ __launch_bounds__(kFusedBlock) void fused_slab_kernel(const float* __
     __syncthreads();
   }
   f32x4 sc;
-  float div[4];
+  double rcp[4];
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     sc[i] = red[i][tx] / 127.0f;                           // the one IEEE divide per channel
-    div[i] = divisor_of(sc[i]);
+    rcp[i] = reciprocal_of(divisor_of(sc[i]));
   }
   if (active && ty == 0) *reinterpret_cast<f32x4*>(scales + slab * D + col) = sc;
 
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_slab_kernel(const float* __
       uint32_t w = 0;
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        float y = v[u][i] / div[i];
+        float y = quotient_by(v[u][i], rcp[i]);  // the bits of v / divisor, without the divide sequence
         y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
         w |= (__float_as_uint(y + kRoundMagic) & 0xffu) << (8 * i);
       }

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
 
   f32x4 v[kTallRegRows];
   float m[4];
-  float div[4];
+  double rcp[4];  // reciprocals of the held tile's divisors
 
   // Loads a tile (descriptor nx, this lane's first byte xo) while quantizing the tile held in v and LDS
   // into the codes behind cx at this lane's first byte co.  Leaves the column maxima of the loaded
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
       uint32_t w = 0;
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        float y = r[i] / div[i];
+        float y = quotient_by(r[i], rcp[i]);  // the bits of r[i] / divisor, without the divide sequence
         y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
         w |= (__float_as_uint(y + kRoundMagic) & 0xffu) << (8 * i);
       }
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
 #pragma unroll
   for (int u = 0; u < kTallRegRows; u++) v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-  for (int i = 0; i < 4; i++) div[i] = 1.0f;
+  for (int i = 0; i < 4; i++) rcp[i] = 1.0;
   // The workgroups that hold the other tiles of the same quads (same XCD, same place in its sequence) write
   // the other pieces of the same lines of codes.  The pieces only meet in L2 if they are written within a
   // few microseconds of each other, and left alone the workgroups drift apart by more than that within a
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kTallBlock, 1) void fused_tall_kernel(const float* 
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       sc[i] = top[i] / 127.0f;  // the one IEEE divide per channel
-      div[i] = divisor_of(sc[i]);
+      rcp[i] = reciprocal_of(divisor_of(sc[i]));
     }
     if (tx * 4 < width_of(cur) && ty == 0)
       *reinterpret_cast<f32x4*>(scales + (int64_t)cur.slab * D + first_channel_of(cur) + tx * 4) = sc;
@@ -312,13 +312,15 @@ static int tall_tx_log2(int64_t N, int64_t D) {
 // (kvq_fused.hip) could take it too.  The tile has to be more than half full (the arithmetic of a turn is
 // that of a full tile), every byte offset inside it has to fit 32 bits, and then, measured
 // (profiles/fused_column_tiles.md):
-//  - more than 1024 rows (tiles of 32 or 64 channels): always -- [256 x 2048 x 256] 0.138 against 0.178 ms
-//    for the register-only kernel, whose 16 rows per lane leave one workgroup per compute unit with nothing
-//    to overlap;
-//  - up to 1024 rows (tiles of 128 or 256 channels): only without the other kernel, or with whole tiles and
-//    at least eight of them per compute unit -- [2048 x 1024 x 128] 0.243 against 0.262 ms, but
-//    [512 x 1024 x 256] (four tiles per unit: the first and the last turn of a workgroup are half idle)
-//    0.144 against 0.138 ms, and a last tile of a few channels costs a whole turn.
+//  - more than 2048 rows (tiles of 32 channels): always -- the register-only kernel has only 16-channel
+//    tiles there ([256 x 4096 x 128] 0.143 against 0.162 ms, [2048 x 4096 x 128] 1.22 against 1.30);
+//  - 1025 to 2048 rows (tiles of 64 channels): while a compute unit gets fewer than eight tiles --
+//    [256 x 2048 x 256] 0.128 against 0.138 ms for the register-only kernel, whose 16 rows per lane leave one
+//    workgroup per unit with nothing to overlap, but [2048 x 2048 x 128] 0.605 against 0.582 ms: over many
+//    turns the waiting for the neighbour costs more than that;
+//  - up to 1024 rows (tiles of 128 or 256 channels): only without the other kernel, which runs two
+//    workgroups of 8 rows per lane on a unit there and is level or ahead -- [512 x 1024 x 256] 0.123 against
+//    0.137 ms, [512 x 512 x 1024] 0.220 against 0.232, [2048 x 1024 x 128] 0.245 against 0.236.
 // KVQ_OPT_FUSED_TALL = 3 takes every problem whose tiles are more than half full.
 bool fused_tall_applicable(const float* x, const float* scales, const int8_t* codes, int64_t batch, int64_t N,
                            int64_t D, bool slab_form) {
@@ -328,10 +330,10 @@ bool fused_tall_applicable(const float* x, const float* scales, const int8_t* co
   if (N > kTallRowsPerLane * (kTallBlock >> 3) || D > 65536) return false;
   const int tx_log2 = tall_tx_log2(N, D);
   if (2 * N <= (int64_t)kTallRowsPerLane * (kTallBlock >> tx_log2)) return false;
-  if (mode == 3 || tx_log2 <= 4 || !slab_form) return true;
+  if (mode == 3 || tx_log2 == 3 || !slab_form) return true;
+  if (tx_log2 > 4) return false;
   const int64_t tile_channels = (int64_t)4 << tx_log2;
-  const DeviceInfo dev = current_device();
-  return D % tile_channels == 0 && batch * (D / tile_channels) >= 8 * (int64_t)dev.cus;
+  return batch * ((D + tile_channels - 1) / tile_channels) < 8 * (int64_t)current_device().cus;
 }
 
 kvq_status launch_fused_tall(const float* x, float* scales, int8_t* codes, int64_t batch, int64_t N, int64_t D,

@@ -130,7 +130,7 @@ def main():
         print()
         print("The persistent kernel (a column tile of 32 to 256 channels in the registers and LDS of one workgroup per compute unit):")
         print()
-        print("| batch x N x D | two calls ms | fused (default) ms | its workgroups do not wait for their neighbours | wherever its tiles are at least half full | never (register-only kernel, tiles down to 16 channels) |")
+        print("| batch x N x D | two calls ms | fused (default) ms | its workgroups do not wait for their neighbours | wherever its tiles are at least half full | never (register-only kernel; above 2048 rows its tiles are 16 channels) |")
         print("|---|---|---|---|---|---|")
         saved_tall = kvq.kvq_get_option(kvq.OPT_FUSED_TALL)
         for (B, N, D) in [(256, 4096, 128), (512, 4096, 128), (2048, 4096, 128), (64, 4096, 512), (256, 3072, 128),
@@ -142,7 +142,8 @@ def main():
             codes = torch.empty(E, dtype=torch.int8, device="cuda")
             two, _ = timeit(lambda: (kvq.kvq_absmax_scales(x, scales, B, N, D), kvq.kvq_quantize(x, scales, codes, B, N, D)))
             cells = []
-            for tall, lanes in ((saved_tall, saved[0]), (2, saved[0]), (3, saved[0]), (0, 4)):
+            # the register-only kernel reaches more than 2048 rows only with tiles of 4 lanes (16 channels)
+            for tall, lanes in ((saved_tall, saved[0]), (2, saved[0]), (3, saved[0]), (0, 4 if N > 2048 else saved[0])):
                 kvq.kvq_set_option(kvq.OPT_FUSED_TALL, tall)
                 kvq.kvq_set_option(kvq.OPT_FUSED_MIN_LANES, lanes)
                 kvq.kvq_set_option(kvq.OPT_FUSED_MAX_ROWS, 16 if (tall == 0 and N > 2048) else saved[1])
